@@ -1,0 +1,167 @@
+"""CPU oracle for Finch's prompt-guided top-r selection (arxiv 2408.00167).
+
+TEST INFRASTRUCTURE ONLY.  This file is the plain, slow definition the HIP path is
+checked against.  It is imported by tests/, by `__graft_entry__.smoke()` and by
+the `cpu_baseline` leg of bench.py, and by nothing else; it shares no code with
+the HIP library and imports nothing from it.
+
+Everything is fp64 numpy.  Inputs are taken exactly as stored: float32 arrays are
+widened, bfloat16 arrays arrive as uint16 bit patterns and are widened exactly, so
+products are exact and only summation order can differ from other
+implementations.  One *problem* is one (request, layer, KV head): Q holds the
+R = G * n_que prompt rows of the G query heads sharing that KV head, stacked.
+
+Steps follow the paper's Method section, "Prompt-Guided Layer-wise top r position
+selection" and "Managing the Cache", with these readings where the text leaves a
+choice (each is listed in the design notes of the repository):
+  * softmax denominator: over the c + m context keys (cache then chunk) only;
+  * head sum: over the G query heads of one KV group (the rows stacked in Q);
+  * the normalisation factor count(A != 0)/(m + c) is one positive constant for
+    all keys of a step (every prompt row sees every context key), so it is
+    dropped: sum_j score_j == R;
+  * d_k in the scale is the head dimension;
+  * top-r ties go to the lowest index, kept rows stay in ascending index order;
+  * r schedule: r_i = min(c_{i-1} + m_i, floor(k * seen_i / n_cont)), which equals
+    the paper's r_{it+1} = m_{it+1}/sigma + c_it whenever m/sigma is an integer
+    and ends at r = k.
+
+Pins (tests/test_oracle_*.py, all `-m "not gpu"`): closed-form softmax values on
+one-hot constructions, uniform scores for identical keys, R = 1 reducing to an
+argsort of raw dot products, scipy's softmax/logsumexp on random inputs,
+pure-Python brute force (explicit full matrix + full sort) on tiny inputs, the
+invariants (rows sum to 1, sum of scores = R, exactly min(r, N) kept, ascending,
+r >= N is the identity), the schedule's closed forms, single-chunk == one-shot,
+sigma = 1 == identity, and planted-mistake tests showing that a dropped scale, a
+transposed operand, a wrong axis, a wrong tie rule or a wrong concatenation order
+each break at least one pin.  `reposition` is pinned by the paper's worked example.
+"""
+from __future__ import annotations
+
+import math
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+__all__ = ["widen", "attention_weights", "key_scores", "top_r", "gather_rows",
+           "step", "schedule", "compress", "reposition"]
+
+
+def widen(x: np.ndarray) -> np.ndarray:
+    """Stored values -> float64, exactly.  uint16 is read as bfloat16 bits."""
+    x = np.asarray(x)
+    if x.dtype == np.uint16:
+        return (x.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    if x.dtype in (np.float32, np.float64):
+        return x.astype(np.float64)
+    raise TypeError(f"unsupported storage dtype {x.dtype}")
+
+
+def attention_weights(Q: np.ndarray, K: np.ndarray) -> np.ndarray:
+    """softmax(Q K^T / sqrt(d_k)) row by row (Background, attention equation).
+
+    Q is [R][d], K is [N][d]; returns the R x N matrix of weights, each row a
+    distribution over the N keys.
+    """
+    Q = widen(Q)
+    K = widen(K)
+    d = Q.shape[1]
+    S = (Q @ K.T) / math.sqrt(float(d))
+    if S.shape[1] == 0:
+        return S
+    mx = S.max(axis=1, keepdims=True)
+    E = np.exp(S - mx)
+    Z = E.sum(axis=1, keepdims=True)
+    return E / Z
+
+
+def key_scores(Q: np.ndarray, K_cache: np.ndarray, K_chunk: np.ndarray) -> np.ndarray:
+    """One relevance score per context key (Method: sum over heads, prompt-guided
+    sub-matrix, aggregation over prompt rows).
+
+    Keys are ordered cache rows first, then chunk rows.  Because Q already stacks
+    the prompt rows of every head of the group, the head sum and the sum over
+    prompt tokens are one column sum of the weight matrix.
+    """
+    K = np.concatenate([np.asarray(K_cache), np.asarray(K_chunk)], axis=0)
+    P = attention_weights(Q, K)
+    return P.sum(axis=0)
+
+
+def top_r(scores: np.ndarray, r: int) -> np.ndarray:
+    """Indices of the r highest scores, ties to the lowest index, returned in
+    ascending index order (Method: t = top-r(A_agg, r)).  r is clamped to
+    [0, N].  Works on whatever precision `scores` has, without converting it.
+    """
+    scores = np.asarray(scores)
+    n = scores.shape[0]
+    r = max(0, min(int(r), n))
+    order = np.argsort(-scores, kind="stable")     # descending, equal scores by index
+    return np.sort(order[:r]).astype(np.int32)
+
+
+def gather_rows(idx: np.ndarray, cache: np.ndarray, chunk: np.ndarray) -> np.ndarray:
+    """Rows idx of [cache ; chunk], copied bit for bit (Managing the Cache)."""
+    both = np.concatenate([np.asarray(cache), np.asarray(chunk)], axis=0)
+    return both[np.asarray(idx, dtype=np.int64)].copy()
+
+
+def step(Q, K_cache, V_cache, K_chunk, V_chunk, r: int):
+    """One prefill step for one problem: score, select, compact.
+
+    Returns (scores fp64 [c+m], idx int32 [min(r, c+m)] ascending, K', V').
+    """
+    scores = key_scores(Q, K_cache, K_chunk)
+    idx = top_r(scores, r)
+    return scores, idx, gather_rows(idx, K_cache, K_chunk), gather_rows(idx, V_cache, V_chunk)
+
+
+def schedule(n_cont: int, m: int, k: int) -> List[int]:
+    """Rows kept after each chunk step (Method: the r update rule; the last value
+    is the target size k, or n_cont if the budget is not smaller)."""
+    if n_cont <= 0:
+        return []
+    out: List[int] = []
+    c = 0
+    seen = 0
+    k = min(int(k), int(n_cont))
+    while seen < n_cont:
+        mi = min(m, n_cont - seen)
+        seen += mi
+        r = min(c + mi, (k * seen) // n_cont)
+        out.append(r)
+        c = r
+    return out
+
+
+def compress(Q, K_doc: np.ndarray, V_doc: np.ndarray, m: int, k: int,
+             rs: Optional[Sequence[int]] = None):
+    """The chunk loop for one problem (Method: Document Segmentation + Compression
+    Output).  Q is either one [R][d] block used at every step or a sequence with
+    one block per step.
+
+    Returns (K~, V~, positions, history) where positions[t] is the document index
+    of kept row t and history is the per-step list of (scores, idx).
+    """
+    K_doc = np.asarray(K_doc)
+    V_doc = np.asarray(V_doc)
+    n_cont = K_doc.shape[0]
+    rs = list(schedule(n_cont, m, k) if rs is None else rs)
+    Kc, Vc = K_doc[:0].copy(), V_doc[:0].copy()
+    pos = np.zeros(0, dtype=np.int64)
+    history: List[Tuple[np.ndarray, np.ndarray]] = []
+    for i, r in enumerate(rs):
+        lo, hi = i * m, min((i + 1) * m, n_cont)
+        q = Q[i] if isinstance(Q, (list, tuple)) else Q
+        scores, idx, Kn, Vn = step(q, Kc, Vc, K_doc[lo:hi], V_doc[lo:hi], r)
+        pos = np.concatenate([pos, np.arange(lo, hi, dtype=np.int64)])[idx]
+        Kc, Vc = Kn, Vn
+        history.append((scores, idx))
+    return Kc, Vc, pos, history
+
+
+def reposition(ranking: Sequence[int]) -> List[int]:
+    """Signed slot moves of the kept cache entries when they are re-packed in
+    relevance-rank order (Managing the Cache, worked example): entry at old slot
+    ranking[t] goes to new slot t; negative = towards the start.
+    """
+    return [t - int(old) for t, old in enumerate(ranking)]

@@ -1,0 +1,364 @@
+"""Pins for the CPU oracle, written as functions of the oracle module `O` so that
+the same checks can be run against deliberately broken copies of it
+(test_oracle_mutations.py).  Expected values here come from closed forms worked
+out by hand, from library routines (scipy, numpy argsort), from pure-Python brute
+force, or from the paper (tests/golden/); none come from the oracle itself.
+"""
+import math
+import os
+
+import numpy as np
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def bf16_bits(x: np.ndarray) -> np.ndarray:
+    """float32 -> bfloat16 bit patterns (round to nearest even), test helper."""
+    u = np.asarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = u + 0x7FFF + ((u >> 16) & 1)
+    return (u >> 16).astype(np.uint16)
+
+
+# ----------------------------------------------------------------- closed forms
+
+def pin_onehot_closed_form(O):
+    # d = 4 so sqrt(d_k) = 2.  Row 0 has logits (2, 0, 0), row 1 has (0, 4, 0).
+    Q = np.array([[2, 0, 0, 0], [0, 4, 0, 0]], dtype=np.float32)
+    K = np.array([[2, 0, 0, 0], [0, 2, 0, 0], [0, 0, 2, 0]], dtype=np.float32)
+    e2, e4 = math.exp(2.0), math.exp(4.0)
+    want = np.array([[e2 / (e2 + 2), 1 / (e2 + 2), 1 / (e2 + 2)],
+                     [1 / (e4 + 2), e4 / (e4 + 2), 1 / (e4 + 2)]])
+    P = O.attention_weights(Q, K)
+    assert P.shape == (2, 3)
+    np.testing.assert_allclose(P, want, rtol=1e-14, atol=0)
+    s = O.key_scores(Q, K[:1], K[1:])
+    np.testing.assert_allclose(s, want.sum(axis=0), rtol=1e-14, atol=0)
+    # the best key overall is key 1 (e4-dominated), then key 0
+    assert list(O.top_r(s, 1)) == [1]
+    assert list(O.top_r(s, 2)) == [0, 1]
+
+
+def pin_two_key_sigmoid(O):
+    # one query, two keys: the weight of key 0 is the logistic function of the
+    # logit difference (q.k0 - q.k1)/sqrt(d).
+    q = np.array([[1.0, 2.0, -1.0, 0.5, 0, 0, 0, 0, 0]], dtype=np.float64)  # d = 9 -> sqrt = 3
+    k0 = np.array([3.0, 0, 0, 0, 0, 0, 0, 0, 0])
+    k1 = np.array([0, 0, 3.0, 0, 0, 0, 0, 0, 0])
+    delta = (3.0 * 1.0 - 3.0 * (-1.0)) / 3.0        # = 2
+    s = O.key_scores(q, np.stack([k0]), np.stack([k1]))
+    np.testing.assert_allclose(s, [1 / (1 + math.exp(-delta)), 1 / (1 + math.exp(delta))],
+                               rtol=1e-14)
+
+
+def pin_identical_keys_uniform(O):
+    rng = np.random.default_rng(5)
+    Q = rng.standard_normal((7, 16)).astype(np.float32)
+    key = rng.standard_normal(16).astype(np.float32)
+    K = np.tile(key, (10, 1))
+    s = O.key_scores(Q, K[:4], K[4:])
+    np.testing.assert_allclose(s, np.full(10, 7 / 10), rtol=1e-13)
+    # exact ties everywhere -> the lowest indices win
+    assert list(O.top_r(np.full(10, 0.7), 4)) == [0, 1, 2, 3]
+
+
+def pin_dominant_key(O):
+    # one key far above the rest takes (almost) all of every row: score -> R
+    rng = np.random.default_rng(6)
+    Q = np.abs(rng.standard_normal((5, 8))) + 0.5
+    K = rng.standard_normal((12, 8)) * 0.01
+    K[9] = 50.0                     # logit >= 50*8*0.5/sqrt(8) for every row
+    s = O.key_scores(Q, K[:3], K[3:])
+    assert abs(s[9] - 5.0) < 1e-9 and s.argmax() == 9
+
+
+def pin_single_row_is_argsort_of_dots(O):
+    rng = np.random.default_rng(7)
+    q = rng.standard_normal((1, 32))
+    K = rng.standard_normal((200, 32))
+    dots = K @ q[0]
+    want = np.sort(np.argsort(-dots, kind="stable")[:37])
+    got = O.top_r(O.key_scores(q, K[:50], K[50:]), 37)
+    assert got.dtype == np.int32 and list(got) == list(want)
+
+
+def pin_scipy_softmax(O):
+    from scipy.special import logsumexp, softmax
+    rng = np.random.default_rng(8)
+    Q = rng.standard_normal((9, 24)) * 2
+    K = rng.standard_normal((41, 24)) * 2
+    S = np.einsum("id,jd->ij", Q, K) / math.sqrt(24)
+    P = O.attention_weights(Q, K)
+    np.testing.assert_allclose(P, softmax(S, axis=1), rtol=1e-12, atol=1e-300)
+    np.testing.assert_allclose(O.key_scores(Q, K[:11], K[11:]),
+                               np.exp(S - logsumexp(S, axis=1, keepdims=True)).sum(axis=0),
+                               rtol=1e-12)
+
+
+# ------------------------------------------------------------------ brute force
+
+def brute_scores(Q, Kc, Kk):
+    """Explicit full softmax matrix in pure Python floats, then column sums."""
+    keys = [list(map(float, row)) for row in Kc] + [list(map(float, row)) for row in Kk]
+    d = len(Q[0])
+    out = [0.0] * len(keys)
+    for qrow in Q:
+        logits = [sum(float(a) * b for a, b in zip(qrow, k)) / math.sqrt(d) for k in keys]
+        top = max(logits)
+        ex = [math.exp(x - top) for x in logits]
+        z = math.fsum(ex)
+        for j, e in enumerate(ex):
+            out[j] += e / z
+    return out
+
+
+def brute_top(scores, r):
+    order = sorted(range(len(scores)), key=lambda j: (-scores[j], j))
+    return sorted(order[:max(0, min(r, len(scores)))])
+
+
+def pin_brute_force_tiny(O):
+    rng = np.random.default_rng(9)
+    for (R, c, m, d, r) in [(1, 0, 5, 4, 2), (3, 4, 6, 8, 5), (4, 7, 0, 8, 3),
+                            (6, 5, 9, 16, 14), (2, 3, 3, 2, 0), (5, 2, 11, 4, 20)]:
+        Q = rng.standard_normal((R, d)).astype(np.float32)
+        Kc = rng.standard_normal((c, d)).astype(np.float32)
+        Kk = rng.standard_normal((m, d)).astype(np.float32)
+        Vc = rng.standard_normal((c, d)).astype(np.float32)
+        Vk = rng.standard_normal((m, d)).astype(np.float32)
+        want = brute_scores(Q, Kc, Kk)
+        scores, idx, Kn, Vn = O.step(Q, Kc, Vc, Kk, Vk, r)
+        np.testing.assert_allclose(scores, want, rtol=1e-12)
+        widx = brute_top(want, r)
+        assert list(idx) == widx
+        allK = [row for row in Kc] + [row for row in Kk]
+        allV = [row for row in Vc] + [row for row in Vk]
+        assert Kn.shape == (len(widx), d) and Vn.shape == (len(widx), d)
+        for t, j in enumerate(widx):
+            assert Kn[t].tobytes() == allK[j].tobytes()
+            assert Vn[t].tobytes() == allV[j].tobytes()
+
+
+def pin_brute_force_bf16(O):
+    rng = np.random.default_rng(10)
+    Qf = rng.standard_normal((3, 8)).astype(np.float32)
+    Kf = rng.standard_normal((9, 8)).astype(np.float32)
+    Qb, Kb = bf16_bits(Qf), bf16_bits(Kf)
+    # widen by hand: bf16 bits are the top half of a float32
+    def wide(bits):
+        return (bits.astype(np.uint32) << 16).view(np.float32)
+    want = brute_scores(wide(Qb), wide(Kb[:4]), wide(Kb[4:]))
+    got = O.key_scores(Qb, Kb[:4], Kb[4:])
+    np.testing.assert_allclose(got, want, rtol=1e-12)
+    # gather keeps the uint16 bits
+    g = O.gather_rows(np.array([1, 8]), Kb[:4], Kb[4:])
+    assert g.dtype == np.uint16 and g.tobytes() == Kb[[1, 8]].tobytes()
+
+
+def pin_widen_bits(O):
+    bits = np.array([0x3F80, 0xC000, 0x3FC0, 0x0000, 0x8000, 0x4049], dtype=np.uint16)
+    want = [1.0, -2.0, 1.5, 0.0, -0.0, 3.140625]
+    got = O.widen(bits)
+    assert got.dtype == np.float64 and list(got) == want
+    assert math.copysign(1.0, got[4]) == -1.0
+    x32 = np.array([0.1, -7.25], dtype=np.float32)
+    assert list(O.widen(x32)) == [float(x32[0]), -7.25]
+
+
+# ------------------------------------------------------------------- invariants
+
+def pin_invariants(O):
+    rng = np.random.default_rng(11)
+    for trial in range(6):
+        R, c, m, d = rng.integers(1, 12), rng.integers(0, 30), rng.integers(1, 40), 16
+        Q = rng.standard_normal((R, d)).astype(np.float32) * 3
+        Kc = rng.standard_normal((c, d)).astype(np.float32)
+        Kk = rng.standard_normal((m, d)).astype(np.float32)
+        K = np.concatenate([Kc, Kk])
+        P = O.attention_weights(Q, K)
+        np.testing.assert_allclose(P.sum(axis=1), np.ones(R), rtol=1e-13)
+        assert (P > 0).all()
+        s = O.key_scores(Q, Kc, Kk)
+        assert abs(s.sum() - R) < 1e-11 * R
+        N = c + m
+        for r in (0, 1, N // 2, N, N + 5):
+            idx = O.top_r(s, r)
+            assert len(idx) == min(r, N)
+            assert (np.diff(idx) > 0).all()
+            kept = np.zeros(N, bool)
+            kept[idx] = True
+            if 0 < len(idx) < N:
+                assert s[kept].min() >= s[~kept].max()
+            if r >= N:
+                assert list(idx) == list(range(N))
+        # permuting keys permutes scores
+        perm = rng.permutation(N)
+        s_perm = O.key_scores(Q, K[perm][:c], K[perm][c:])
+        np.testing.assert_allclose(s_perm, s[perm], rtol=1e-11)
+        # duplicating every query row doubles every score
+        np.testing.assert_allclose(O.key_scores(np.concatenate([Q, Q]), Kc, Kk), 2 * s, rtol=1e-12)
+        # a per-row constant shift of the logits changes nothing: extra channel that is
+        # 1 in every key and arbitrary in each query
+        extra = rng.standard_normal((R, 1)).astype(np.float32) * 4
+        Q2 = np.concatenate([Q * math.sqrt((d + 1) / d), extra], axis=1)
+        K2 = np.concatenate([K, np.ones((N, 1), np.float32)], axis=1)
+        np.testing.assert_allclose(O.key_scores(Q2.astype(np.float64), K2[:c], K2[c:]), s, rtol=1e-6)
+
+
+def pin_identity_when_budget_covers(O):
+    rng = np.random.default_rng(12)
+    Q = rng.standard_normal((4, 8)).astype(np.float32)
+    Kc, Kk = rng.standard_normal((5, 8)).astype(np.float32), rng.standard_normal((6, 8)).astype(np.float32)
+    Vc, Vk = rng.standard_normal((5, 8)).astype(np.float32), rng.standard_normal((6, 8)).astype(np.float32)
+    for r in (11, 12, 1000):
+        _, idx, Kn, Vn = O.step(Q, Kc, Vc, Kk, Vk, r)
+        assert list(idx) == list(range(11))
+        assert Kn.tobytes() == np.concatenate([Kc, Kk]).tobytes()
+        assert Vn.tobytes() == np.concatenate([Vc, Vk]).tobytes()
+
+
+def pin_tie_rule(O):
+    s = np.array([0.5, 0.9, 0.5, 0.9, 0.5, 0.1], dtype=np.float32)
+    assert list(O.top_r(s, 1)) == [1]
+    assert list(O.top_r(s, 2)) == [1, 3]
+    assert list(O.top_r(s, 3)) == [0, 1, 3]
+    assert list(O.top_r(s, 4)) == [0, 1, 2, 3]
+    assert list(O.top_r(s, 5)) == [0, 1, 2, 3, 4]
+    assert O.top_r(s, 0).shape == (0,)
+    # float32 input is ranked as float32 (no hidden rounding or widening effects)
+    t = np.array([1.0, 1.0 + 2 ** -23, 1.0], dtype=np.float32)
+    assert list(O.top_r(t, 2)) == [0, 1]
+
+
+# --------------------------------------------------------------------- schedule
+
+def pin_schedule_golden(O):
+    with open(os.path.join(GOLDEN, "schedule_examples.txt")) as f:
+        rows = [list(map(int, ln.split())) for ln in f if ln.strip() and not ln.startswith("#")]
+    assert len(rows) == 4
+    for n_cont, m, k, first, second, last, count in rows:
+        rs = O.schedule(n_cont, m, k)
+        assert len(rs) == count and rs[0] == first and rs[1] == second and rs[-1] == last
+        sigma = n_cont / k
+        c = 0
+        for r in rs:                      # the paper's rule, increments m/sigma
+            assert r == c + round(m / sigma)
+            c = r
+
+
+def pin_schedule_properties(O):
+    for n_cont, m, k in [(1000, 256, 100), (2049, 2048, 64), (5, 8, 2), (4096, 512, 5000),
+                         (777, 100, 777), (65536, 2048, 2048), (2048, 2048, 64), (3000, 7, 1)]:
+        rs = O.schedule(n_cont, m, k)
+        assert len(rs) == -(-n_cont // m)
+        c = seen = 0
+        for i, r in enumerate(rs):
+            mi = min(m, n_cont - seen)
+            seen += mi
+            assert 0 <= r <= c + mi               # never more than the candidates
+            assert r == min(c + mi, (min(k, n_cont) * seen) // n_cont)
+            c = r
+        assert rs[-1] == min(k, n_cont)
+        assert all(b >= a for a, b in zip(rs, rs[1:]))    # monotone
+        if k >= n_cont:                                   # no compression: keep everything seen
+            assert rs == [min((i + 1) * m, n_cont) for i in range(len(rs))]
+    assert O.schedule(0, 16, 4) == []
+
+
+# --------------------------------------------------------------- chunk recurrence
+
+def pin_single_chunk_is_one_shot(O):
+    rng = np.random.default_rng(13)
+    Q = rng.standard_normal((5, 8)).astype(np.float32)
+    K = rng.standard_normal((40, 8)).astype(np.float32)
+    V = rng.standard_normal((40, 8)).astype(np.float32)
+    Kt, Vt, pos, hist = O.compress(Q, K, V, m=40, k=9)
+    want = brute_top(brute_scores(Q, K[:0], K), 9)
+    assert list(pos) == want and len(hist) == 1
+    assert Kt.tobytes() == K[want].tobytes() and Vt.tobytes() == V[want].tobytes()
+
+
+def pin_sigma_one_is_identity(O):
+    rng = np.random.default_rng(14)
+    Q = rng.standard_normal((3, 4)).astype(np.float32)
+    K = rng.standard_normal((23, 4)).astype(np.float32)
+    V = rng.standard_normal((23, 4)).astype(np.float32)
+    for k in (23, 50):
+        Kt, Vt, pos, _ = O.compress(Q, K, V, m=5, k=k)
+        assert list(pos) == list(range(23))
+        assert Kt.tobytes() == K.tobytes() and Vt.tobytes() == V.tobytes()
+
+
+def pin_recurrence_brute_force(O):
+    """Whole chunk loop against a pure-Python re-statement: at each step the
+    candidates are the rows kept so far plus the new chunk, all re-scored."""
+    rng = np.random.default_rng(15)
+    Q = rng.standard_normal((4, 8)).astype(np.float32)
+    K = rng.standard_normal((50, 8)).astype(np.float32)
+    V = rng.standard_normal((50, 8)).astype(np.float32)
+    m, k = 12, 10
+    rs = [2, 4, 7, 9, 10]                 # floor(10 * seen / 50), seen = 12,24,36,48,50
+    assert O.schedule(50, m, k) == rs
+    kept = []
+    for i, r in enumerate(rs):
+        cand = kept + list(range(i * m, min((i + 1) * m, 50)))
+        sc = brute_scores(Q, K[:0], K[cand])
+        kept = [cand[j] for j in brute_top(sc, r)]
+    Kt, Vt, pos, hist = O.compress(Q, K, V, m, k)
+    assert list(pos) == kept and len(hist) == 5
+    assert Kt.tobytes() == K[kept].tobytes() and Vt.tobytes() == V[kept].tobytes()
+
+
+def pin_cached_row_can_be_evicted(O):
+    # step 1 keeps row 0 (the only strong key of chunk 1); chunk 2 holds two stronger
+    # keys, and with r = 2 the previously cached row must go.
+    d = 4
+    Q = np.array([[4.0, 0, 0, 0]])
+    K = np.zeros((6, d))
+    K[0, 0] = 1.0
+    K[3, 0] = 3.0
+    K[5, 0] = 2.0
+    V = np.arange(24, dtype=np.float64).reshape(6, d)
+    Kt, Vt, pos, hist = O.compress(Q, K, V, m=3, k=2, rs=[1, 2])
+    assert list(hist[0][1]) == [0]
+    assert list(pos) == [3, 5]
+    assert Vt.tobytes() == V[[3, 5]].tobytes()
+
+
+def pin_per_step_queries(O):
+    # a different Q per step: step 2 ranks by its own Q, not by step 1's
+    d = 2
+    K = np.array([[2.0, 0], [0, 2.0], [2.0, 0], [0, 2.0]])
+    V = K.copy()
+    Qa, Qb = np.array([[5.0, 0]]), np.array([[0, 5.0]])
+    _, _, pos, _ = O.compress([Qa, Qb], K, V, m=2, k=1, rs=[1, 1])
+    assert list(pos) == [3]
+    _, _, pos, _ = O.compress([Qa, Qa], K, V, m=2, k=1, rs=[1, 1])
+    assert list(pos) == [0]
+
+
+def pin_split_and_resume(O):
+    rng = np.random.default_rng(16)
+    Q = rng.standard_normal((3, 8)).astype(np.float32)
+    K = rng.standard_normal((64, 8)).astype(np.float32)
+    V = rng.standard_normal((64, 8)).astype(np.float32)
+    rs = O.schedule(64, 16, 8)
+    Kt, Vt, pos, _ = O.compress(Q, K, V, 16, 8)
+    # run two steps, "save" the cache, continue with explicit step calls
+    Kc, Vc, p2, _ = O.compress(Q, K[:32], V[:32], 16, 8, rs=rs[:2])
+    for i in (2, 3):
+        _, idx, Kc, Vc = O.step(Q, Kc, Vc, K[16 * i:16 * i + 16], V[16 * i:16 * i + 16], rs[i])
+        p2 = np.concatenate([p2, np.arange(16 * i, 16 * i + 16)])[idx]
+    assert list(p2) == list(pos) and Kc.tobytes() == Kt.tobytes() and Vc.tobytes() == Vt.tobytes()
+
+
+# ------------------------------------------------------------ paper's worked example
+
+def pin_reposition_example(O):
+    with open(os.path.join(GOLDEN, "reposition_example.txt")) as f:
+        rows = [list(map(int, ln.split())) for ln in f if ln.strip() and not ln.startswith("#")]
+    ranking = [r[0] for r in rows]
+    assert ranking == [3, 5, 0]
+    assert O.reposition(ranking) == [r[1] for r in rows]
+
+
+ALL_PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_") and callable(v)]
