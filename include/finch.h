@@ -1,0 +1,129 @@
+/*
+ * finch.h - C ABI of the MI355X (gfx950) library for Finch's prompt-guided
+ * KV-cache selection step (arxiv 2408.00167, Method section).
+ *
+ * One *problem* is one (request, layer, KV head).  At a prefill step the problem
+ * has c rows already in its compressed cache and m rows in the new document
+ * chunk; N = c + m candidate keys, ordered cache rows first, then chunk rows
+ * (the column order of the paper's prompt-guided sub-matrix A^cont, whose columns
+ * run over the chunk and the tokens accumulated in the cache).  Its query block
+ * stacks the n_que prompt rows of each of the G query heads that share the KV
+ * head: R = G * n_que rows.
+ *
+ * All data pointers inside finch_problem are DEVICE pointers owned by the caller.
+ * Descriptor arrays are passed twice: `host_desc` (host memory, read during the
+ * call for validation and launch sizing) and `dev_desc` (device memory holding the
+ * same bytes, read by the kernels).  Every entry point enqueues work on `stream`
+ * (a hipStream_t passed as void*, NULL = the null stream) and returns without
+ * synchronising; nothing is allocated after finch_create.  Outputs are valid once
+ * the caller has synchronised the stream.  Results are bit-identical run to run.
+ *
+ * Errors: every function returns a finch_status.  Argument errors are detected on
+ * the host before anything is launched.  Non-finite inputs are undefined
+ * behaviour (not checked).
+ */
+#ifndef FINCH_H
+#define FINCH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FINCH_OK = 0,
+  FINCH_ERR_INVALID_ARG = -1, /* null/misaligned pointer, negative size, aliasing */
+  FINCH_ERR_UNSUPPORTED = -2, /* dtype / head_dim / group size not built          */
+  FINCH_ERR_CAPACITY = -3,    /* a size exceeds what one launch can index         */
+  FINCH_ERR_WORKSPACE = -4,   /* workspace missing, misaligned or too small       */
+  FINCH_ERR_HIP = -5          /* a HIP call failed; see finch_last_hip_error      */
+} finch_status;
+
+typedef enum { FINCH_F32 = 0, FINCH_BF16 = 1 } finch_dtype;
+
+typedef struct finch_ctx finch_ctx; /* opaque; bound to the device current at finch_create */
+
+typedef struct {
+  int32_t dtype;      /* finch_dtype of Q, K, V.  Scores are always fp32.          */
+  int32_t head_dim;   /* d_k: 64 or 128                                            */
+  int32_t group_size; /* G = query heads per KV head (1 = MHA), 1..64              */
+  int32_t reserved;   /* must be 0                                                 */
+} finch_config;
+
+typedef struct {
+  const void* q;       /* [G*n_que][d] row-major: head 0's prompt rows, head 1's, ... */
+  const void* k_cache; /* [c][d] keys kept so far (may be NULL when c == 0)           */
+  const void* v_cache; /* [c][d]                                                      */
+  const void* k_chunk; /* [m][d] keys of the new chunk (may be NULL when m == 0)      */
+  const void* v_chunk; /* [m][d]                                                      */
+  void* k_out;         /* [>= min(r, c+m)][d]; must not overlap any source above      */
+  void* v_out;         /* [>= min(r, c+m)][d]                                         */
+  float* scores;       /* [c+m] out.  finch_step accepts NULL (kept in workspace)     */
+  int32_t* idx;        /* [min(r, c+m)] out: kept candidates, ascending, in [0, c+m)  */
+  int32_t n_que;       /* prompt rows per query head, >= 1                            */
+  int32_t c;           /* cache rows, >= 0                                            */
+  int32_t m;           /* chunk rows, >= 0 (m == 0: a cache-only step)                */
+  int32_t r;           /* rows to keep, >= 0; values above c+m mean "keep all"        */
+} finch_problem;
+
+/* Row bases (q, k_*, v_*, *_out) must be 16-byte aligned, scores and idx 4-byte. */
+
+finch_status finch_create(const finch_config* cfg, finch_ctx** out);
+finch_status finch_destroy(finch_ctx* ctx);
+
+/* Bytes of device workspace that any of the four calls below needs for this batch
+ * (an upper bound valid for every call whose per-problem n_que, c+m and r do not
+ * exceed the maxima of `host_desc`).  The workspace must be 256-byte aligned. */
+finch_status finch_workspace_size(const finch_ctx* ctx, const finch_problem* host_desc,
+                                  int32_t n_problems, size_t* bytes);
+
+/* Scoring (Method: attention of the prompt rows over the context keys, summed
+ * over the heads of the group and over the prompt rows):
+ *   scores[j] = sum_{i<R} softmax_j( q_i . k_j / sqrt(d_k) ),  j < c+m,
+ * the softmax running over the c+m context keys, so sum_j scores[j] == R.
+ * Writes desc.scores (must be non-NULL here). */
+finch_status finch_score(finch_ctx* ctx, const finch_problem* host_desc,
+                         const finch_problem* dev_desc, int32_t n_problems,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Selection (Method: t = top-r(A_agg, r)): reads desc.scores (any finite fp32),
+ * writes the indices of the min(r, c+m) largest into desc.idx in ascending order;
+ * equal scores are resolved towards the lower index (+0 and -0 are equal). */
+finch_status finch_topk(finch_ctx* ctx, const finch_problem* host_desc,
+                        const finch_problem* dev_desc, int32_t n_problems,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* Compaction (Method: Managing the Cache - the K,V pairs of the selected
+ * positions are kept): k_out[t] = K[idx[t]], v_out[t] = V[idx[t]] for
+ * t < min(r, c+m), where row j of K is k_cache[j] if j < c else k_chunk[j-c].
+ * A bit-for-bit copy; rows of k_out/v_out beyond that are left untouched. */
+finch_status finch_compact(finch_ctx* ctx, const finch_problem* host_desc,
+                           const finch_problem* dev_desc, int32_t n_problems,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* One prefill step (Method: Document Segmentation - the pairs kept at step i-1
+ * compete with chunk i): score, then top-r, then compaction, stream-ordered with
+ * no host synchronisation.  desc.scores may be NULL. */
+finch_status finch_step(finch_ctx* ctx, const finch_problem* host_desc,
+                        const finch_problem* dev_desc, int32_t n_problems,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* Host-only: rows kept after each chunk step (Method: the update rule
+ * r_{it+1} = m_{it+1}/sigma + c_it with sigma = n_cont/k, ending at r = k), in
+ * integers: r_i = min(c_{i-1} + m_i, floor(min(k, n_cont) * seen_i / n_cont)).
+ * Writes ceil(n_cont/m) values; `r_len` is the capacity of r_out. */
+finch_status finch_schedule(int64_t n_cont, int32_t m, int64_t k, int32_t* r_out,
+                            int32_t r_len);
+
+/* The hipError_t (as int) of the last failed HIP call seen by this context. */
+int32_t finch_last_hip_error(const finch_ctx* ctx);
+const char* finch_status_string(finch_status s);
+/* Library version, major*10000 + minor*100 + patch. */
+int32_t finch_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FINCH_H */

@@ -1,0 +1,355 @@
+// Host driver behind the C ABI: argument checks, launch sizing, workspace layout,
+// stream-ordered launches.  No allocation and no synchronisation after
+// finch_create.
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <new>
+
+#include "finch_internal.h"
+
+struct finch_ctx {
+  finch_config cfg;
+  int device;
+  size_t max_lds;   // largest dynamic LDS a workgroup may ask for
+  int last_hip;     // hipError_t of the last failed HIP call
+  int row_bytes;    // bytes of one K or V row
+};
+
+namespace {
+
+using finch::LaunchParams;
+
+enum Need : unsigned {
+  kNeedQK = 1u,      // q, k_cache, k_chunk are read
+  kNeedScoresOut = 2u,  // desc.scores must be non-NULL
+  kNeedIdx = 4u,     // desc.idx is written or read
+  kNeedGather = 8u,  // v_*, k_out, v_out are used
+};
+
+struct Plan {
+  int32_t n_max = 0, rows_max = 0, rpad_max = 0, r_max = 0, tiles_max = 0, row_chunk = 32;
+  int32_t score_stride = 0;
+  size_t lds_bytes = 0;
+  size_t off_stats = 0, off_lse = 0, off_scores = 0, total = 0;
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+inline bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
+  if (!a || !b || na == 0 || nb == 0) return false;
+  const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+  return a0 < b0 + nb && b0 < a0 + na;
+}
+
+size_t score_lds(const finch_ctx* ctx, int row_chunk) {
+  const size_t d = static_cast<size_t>(ctx->cfg.head_dim);
+  const size_t q_row = ctx->cfg.dtype == FINCH_BF16 ? d * 2 + 16 : d * 4;
+  // per staged row: the row itself + 4 per-wave (max,sum) pairs (pass 1) which also
+  // covers the 4-byte lse entry of pass 2
+  return static_cast<size_t>(row_chunk) * (q_row + 4 * sizeof(float2));
+}
+
+finch_status make_plan(const finch_ctx* ctx, const finch_problem* hd, int32_t n, Plan& pl) {
+  const int G = ctx->cfg.group_size;
+  int64_t n_max = 0, rows_max = 0, r_max = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    const finch_problem& pb = hd[i];
+    if (pb.n_que < 1 || pb.c < 0 || pb.m < 0 || pb.r < 0) return FINCH_ERR_INVALID_ARG;
+    const int64_t N = static_cast<int64_t>(pb.c) + pb.m;
+    const int64_t R = static_cast<int64_t>(G) * pb.n_que;
+    if (N > (1 << 24) || R > (1 << 20)) return FINCH_ERR_CAPACITY;
+    if (N > n_max) n_max = N;
+    if (R > rows_max) rows_max = R;
+    const int64_t rr = pb.r < N ? pb.r : N;
+    if (rr > r_max) r_max = rr;
+  }
+  pl.n_max = static_cast<int32_t>(n_max);
+  pl.rows_max = static_cast<int32_t>(rows_max);
+  pl.rpad_max = static_cast<int32_t>((rows_max + 31) / 32 * 32);
+  pl.r_max = static_cast<int32_t>(r_max);
+  pl.tiles_max = static_cast<int32_t>((n_max + finch::kTileKeys - 1) / finch::kTileKeys);
+  pl.score_stride = static_cast<int32_t>((n_max + 63) / 64 * 64);
+  int rc = pl.rpad_max < finch::kMaxRowChunk ? pl.rpad_max : finch::kMaxRowChunk;
+  if (rc < 32) rc = 32;
+  while (rc > 32 && score_lds(ctx, rc) > ctx->max_lds) rc -= 32;
+  if (score_lds(ctx, rc) > ctx->max_lds) return FINCH_ERR_UNSUPPORTED;
+  pl.row_chunk = rc;
+  pl.lds_bytes = score_lds(ctx, rc);
+  // grids are 1-D: keep them below 2^31
+  const int64_t pg = (static_cast<int64_t>(n) + 7) / 8 * 8;
+  if (pg * (pl.tiles_max > 0 ? pl.tiles_max : 1) >= (int64_t{1} << 31)) return FINCH_ERR_CAPACITY;
+  const int64_t gb = (static_cast<int64_t>(pl.r_max) + finch::kGatherRows - 1) / finch::kGatherRows;
+  if (gb * n >= (int64_t{1} << 31)) return FINCH_ERR_CAPACITY;
+  size_t off = 0;
+  pl.off_stats = off;
+  off = align_up(off + static_cast<size_t>(n) * pl.tiles_max * pl.rpad_max * sizeof(float2), 256);
+  pl.off_lse = off;
+  off = align_up(off + static_cast<size_t>(n) * pl.rpad_max * sizeof(float), 256);
+  pl.off_scores = off;
+  off = align_up(off + static_cast<size_t>(n) * pl.score_stride * sizeof(float), 256);
+  pl.total = off;
+  return FINCH_OK;
+}
+
+finch_status validate(const finch_ctx* ctx, const finch_problem* hd, int32_t n, unsigned need) {
+  const size_t rb = static_cast<size_t>(ctx->row_bytes);
+  for (int32_t i = 0; i < n; ++i) {
+    const finch_problem& pb = hd[i];
+    const int64_t N = static_cast<int64_t>(pb.c) + pb.m;
+    const int64_t rr = pb.r < N ? pb.r : N;
+    if (need & kNeedQK) {
+      if (N > 0) {
+        if (!pb.q || !aligned(pb.q, 16)) return FINCH_ERR_INVALID_ARG;
+        if (pb.c > 0 && (!pb.k_cache || !aligned(pb.k_cache, 16))) return FINCH_ERR_INVALID_ARG;
+        if (pb.m > 0 && (!pb.k_chunk || !aligned(pb.k_chunk, 16))) return FINCH_ERR_INVALID_ARG;
+      }
+    }
+    if ((need & kNeedScoresOut) && N > 0) {
+      if (!pb.scores) return FINCH_ERR_INVALID_ARG;
+    }
+    if (pb.scores && !aligned(pb.scores, 4)) return FINCH_ERR_INVALID_ARG;
+    if ((need & kNeedIdx) && rr > 0) {
+      if (!pb.idx || !aligned(pb.idx, 4)) return FINCH_ERR_INVALID_ARG;
+    }
+    if ((need & kNeedGather) && rr > 0) {
+      if (!pb.k_out || !pb.v_out || !aligned(pb.k_out, 16) || !aligned(pb.v_out, 16))
+        return FINCH_ERR_INVALID_ARG;
+      if (pb.c > 0 && (!pb.k_cache || !pb.v_cache || !aligned(pb.k_cache, 16) ||
+                       !aligned(pb.v_cache, 16)))
+        return FINCH_ERR_INVALID_ARG;
+      if (pb.m > 0 && (!pb.k_chunk || !pb.v_chunk || !aligned(pb.k_chunk, 16) ||
+                       !aligned(pb.v_chunk, 16)))
+        return FINCH_ERR_INVALID_ARG;
+      const size_t ob = static_cast<size_t>(rr) * rb;
+      const void* srcs[4] = {pb.k_cache, pb.v_cache, pb.k_chunk, pb.v_chunk};
+      const size_t lens[4] = {static_cast<size_t>(pb.c) * rb, static_cast<size_t>(pb.c) * rb,
+                              static_cast<size_t>(pb.m) * rb, static_cast<size_t>(pb.m) * rb};
+      for (int s = 0; s < 4; ++s) {
+        if (overlaps(pb.k_out, ob, srcs[s], lens[s]) || overlaps(pb.v_out, ob, srcs[s], lens[s]))
+          return FINCH_ERR_INVALID_ARG;
+      }
+      if (overlaps(pb.k_out, ob, pb.v_out, ob)) return FINCH_ERR_INVALID_ARG;
+    }
+  }
+  return FINCH_OK;
+}
+
+finch_status check_common(const finch_ctx* ctx, const finch_problem* hd, const finch_problem* dd,
+                          int32_t n) {
+  if (!ctx || n < 0) return FINCH_ERR_INVALID_ARG;
+  if (n > 0 && (!hd || !dd)) return FINCH_ERR_INVALID_ARG;
+  if (n > 0 && !aligned(dd, 8)) return FINCH_ERR_INVALID_ARG;
+  return FINCH_OK;
+}
+
+finch_status check_workspace(const Plan& pl, const void* ws, size_t ws_bytes) {
+  if (pl.total == 0) return FINCH_OK;
+  if (!ws || !aligned(ws, 256) || ws_bytes < pl.total) return FINCH_ERR_WORKSPACE;
+  return FINCH_OK;
+}
+
+LaunchParams make_params(const finch_ctx* ctx, const finch_problem* dd, int32_t n, const Plan& pl,
+                         void* ws) {
+  LaunchParams p;
+  std::memset(&p, 0, sizeof(p));
+  p.probs = dd;
+  p.n_problems = n;
+  p.group = ctx->cfg.group_size;
+  p.tiles_max = pl.tiles_max;
+  p.rpad_max = pl.rpad_max;
+  p.row_chunk = pl.row_chunk;
+  p.score_stride = pl.score_stride;
+  p.scale_log2 = static_cast<float>(1.4426950408889634 / std::sqrt(static_cast<double>(ctx->cfg.head_dim)));
+  char* base = static_cast<char*>(ws);
+  p.stats = reinterpret_cast<float2*>(base + pl.off_stats);
+  p.lse = reinterpret_cast<float*>(base + pl.off_lse);
+  p.ws_scores = reinterpret_cast<float*>(base + pl.off_scores);
+  return p;
+}
+
+finch_status hip_fail(finch_ctx* ctx, hipError_t e) {
+  ctx->last_hip = static_cast<int>(e);
+  return FINCH_ERR_HIP;
+}
+
+finch_status run_score(finch_ctx* ctx, const LaunchParams& p, const Plan& pl, hipStream_t s) {
+  if (p.n_problems == 0 || pl.tiles_max == 0) return FINCH_OK;
+  hipError_t e;
+  const int d = ctx->cfg.head_dim;
+  if (ctx->cfg.dtype == FINCH_BF16) {
+    e = finch::launch_rowstats_bf16(d, p, pl.lds_bytes, s);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    e = finch::launch_lse(p, s);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    e = finch::launch_colsum_bf16(d, p, pl.lds_bytes, s);
+  } else {
+    e = finch::launch_rowstats_f32(d, p, pl.lds_bytes, s);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    e = finch::launch_lse(p, s);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    e = finch::launch_colsum_f32(d, p, pl.lds_bytes, s);
+  }
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  return FINCH_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+finch_status finch_create(const finch_config* cfg, finch_ctx** out) {
+  if (!cfg || !out) return FINCH_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (cfg->reserved != 0) return FINCH_ERR_INVALID_ARG;
+  if (cfg->dtype != FINCH_F32 && cfg->dtype != FINCH_BF16) return FINCH_ERR_UNSUPPORTED;
+  if (cfg->head_dim != 64 && cfg->head_dim != 128) return FINCH_ERR_UNSUPPORTED;
+  if (cfg->group_size < 1 || cfg->group_size > 64) return FINCH_ERR_UNSUPPORTED;
+  finch_ctx* ctx = new (std::nothrow) finch_ctx;
+  if (!ctx) return FINCH_ERR_INVALID_ARG;
+  ctx->cfg = *cfg;
+  ctx->last_hip = 0;
+  ctx->device = -1;
+  ctx->max_lds = 64 * 1024;
+  ctx->row_bytes = cfg->head_dim * (cfg->dtype == FINCH_BF16 ? 2 : 4);
+  hipError_t e = hipGetDevice(&ctx->device);
+  if (e == hipSuccess) {
+    int v = 0;
+    e = hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, ctx->device);
+    if (e == hipSuccess && v > 0) ctx->max_lds = static_cast<size_t>(v);
+  }
+  if (e == hipSuccess) {
+    e = cfg->dtype == FINCH_BF16 ? finch::set_max_lds_bf16(ctx->max_lds)
+                                 : finch::set_max_lds_f32(ctx->max_lds);
+  }
+  if (e != hipSuccess) {
+    // No usable GPU: there is no fallback path.  Report and hand nothing out.
+    (void)hipGetLastError();
+    delete ctx;
+    return FINCH_ERR_HIP;
+  }
+  *out = ctx;
+  return FINCH_OK;
+}
+
+finch_status finch_destroy(finch_ctx* ctx) {
+  delete ctx;
+  return FINCH_OK;
+}
+
+finch_status finch_workspace_size(const finch_ctx* ctx, const finch_problem* host_desc,
+                                  int32_t n_problems, size_t* bytes) {
+  if (!ctx || !bytes || n_problems < 0 || (n_problems > 0 && !host_desc))
+    return FINCH_ERR_INVALID_ARG;
+  Plan pl;
+  const finch_status st = make_plan(ctx, host_desc, n_problems, pl);
+  if (st != FINCH_OK) return st;
+  *bytes = pl.total;
+  return FINCH_OK;
+}
+
+finch_status finch_score(finch_ctx* ctx, const finch_problem* host_desc,
+                         const finch_problem* dev_desc, int32_t n, void* ws, size_t ws_bytes,
+                         void* stream) {
+  finch_status st = check_common(ctx, host_desc, dev_desc, n);
+  if (st != FINCH_OK) return st;
+  Plan pl;
+  if ((st = make_plan(ctx, host_desc, n, pl)) != FINCH_OK) return st;
+  if ((st = validate(ctx, host_desc, n, kNeedQK | kNeedScoresOut)) != FINCH_OK) return st;
+  if ((st = check_workspace(pl, ws, ws_bytes)) != FINCH_OK) return st;
+  const LaunchParams p = make_params(ctx, dev_desc, n, pl, ws);
+  return run_score(ctx, p, pl, static_cast<hipStream_t>(stream));
+}
+
+finch_status finch_topk(finch_ctx* ctx, const finch_problem* host_desc,
+                        const finch_problem* dev_desc, int32_t n, void* ws, size_t ws_bytes,
+                        void* stream) {
+  finch_status st = check_common(ctx, host_desc, dev_desc, n);
+  if (st != FINCH_OK) return st;
+  Plan pl;
+  if ((st = make_plan(ctx, host_desc, n, pl)) != FINCH_OK) return st;
+  if ((st = validate(ctx, host_desc, n, kNeedScoresOut | kNeedIdx)) != FINCH_OK) return st;
+  if ((st = check_workspace(pl, ws, ws_bytes)) != FINCH_OK) return st;
+  if (n == 0 || pl.r_max == 0) return FINCH_OK;
+  const LaunchParams p = make_params(ctx, dev_desc, n, pl, ws);
+  const hipError_t e = finch::launch_select(p, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? FINCH_OK : hip_fail(ctx, e);
+}
+
+finch_status finch_compact(finch_ctx* ctx, const finch_problem* host_desc,
+                           const finch_problem* dev_desc, int32_t n, void* ws, size_t ws_bytes,
+                           void* stream) {
+  finch_status st = check_common(ctx, host_desc, dev_desc, n);
+  if (st != FINCH_OK) return st;
+  Plan pl;
+  if ((st = make_plan(ctx, host_desc, n, pl)) != FINCH_OK) return st;
+  if ((st = validate(ctx, host_desc, n, kNeedIdx | kNeedGather)) != FINCH_OK) return st;
+  if ((st = check_workspace(pl, ws, ws_bytes)) != FINCH_OK) return st;
+  if (n == 0 || pl.r_max == 0) return FINCH_OK;
+  const LaunchParams p = make_params(ctx, dev_desc, n, pl, ws);
+  const hipError_t e =
+      finch::launch_gather(p, ctx->row_bytes, pl.r_max, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? FINCH_OK : hip_fail(ctx, e);
+}
+
+finch_status finch_step(finch_ctx* ctx, const finch_problem* host_desc,
+                        const finch_problem* dev_desc, int32_t n, void* ws, size_t ws_bytes,
+                        void* stream) {
+  finch_status st = check_common(ctx, host_desc, dev_desc, n);
+  if (st != FINCH_OK) return st;
+  Plan pl;
+  if ((st = make_plan(ctx, host_desc, n, pl)) != FINCH_OK) return st;
+  if ((st = validate(ctx, host_desc, n, kNeedQK | kNeedIdx | kNeedGather)) != FINCH_OK) return st;
+  if ((st = check_workspace(pl, ws, ws_bytes)) != FINCH_OK) return st;
+  if (n == 0) return FINCH_OK;
+  const LaunchParams p = make_params(ctx, dev_desc, n, pl, ws);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if ((st = run_score(ctx, p, pl, s)) != FINCH_OK) return st;
+  if (pl.r_max == 0) return FINCH_OK;
+  hipError_t e = finch::launch_select(p, s);
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  e = finch::launch_gather(p, ctx->row_bytes, pl.r_max, s);
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  return FINCH_OK;
+}
+
+finch_status finch_schedule(int64_t n_cont, int32_t m, int64_t k, int32_t* r_out, int32_t r_len) {
+  if (n_cont < 0 || m < 1 || k < 0 || r_len < 0) return FINCH_ERR_INVALID_ARG;
+  if (n_cont > (int64_t{1} << 40)) return FINCH_ERR_CAPACITY;
+  const int64_t steps = (n_cont + m - 1) / m;
+  if (steps > r_len) return FINCH_ERR_CAPACITY;
+  if (steps > 0 && !r_out) return FINCH_ERR_INVALID_ARG;
+  const int64_t budget = k < n_cont ? k : n_cont;
+  int64_t kept = 0, seen = 0;
+  for (int64_t i = 0; i < steps; ++i) {
+    const int64_t mi = (n_cont - seen) < m ? (n_cont - seen) : m;
+    seen += mi;
+    // floor(budget * seen / n_cont) without overflow: both factors are < 2^41
+    const __int128 prod = static_cast<__int128>(budget) * seen;
+    int64_t r = static_cast<int64_t>(prod / n_cont);
+    if (r > kept + mi) r = kept + mi;
+    if (r > INT32_MAX) return FINCH_ERR_CAPACITY;
+    r_out[i] = static_cast<int32_t>(r);
+    kept = r;
+  }
+  return FINCH_OK;
+}
+
+int32_t finch_last_hip_error(const finch_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+
+const char* finch_status_string(finch_status s) {
+  switch (s) {
+    case FINCH_OK: return "ok";
+    case FINCH_ERR_INVALID_ARG: return "invalid argument";
+    case FINCH_ERR_UNSUPPORTED: return "unsupported configuration";
+    case FINCH_ERR_CAPACITY: return "size exceeds capacity";
+    case FINCH_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case FINCH_ERR_HIP: return "HIP call failed";
+  }
+  return "unknown status";
+}
+
+int32_t finch_version(void) { return 100; }
+
+}  // extern "C"

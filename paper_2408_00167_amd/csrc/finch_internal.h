@@ -1,0 +1,60 @@
+// Internal declarations shared by the host driver and the kernel files.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "finch.h"
+
+namespace finch {
+
+// Keys handled by one workgroup of the scoring kernels.
+constexpr int kTileKeys = 256;
+// Prompt rows staged in LDS at a time (larger R is processed in several chunks).
+constexpr int kMaxRowChunk = 512;
+// Rows copied by one workgroup of the compaction kernel.
+constexpr int kGatherRows = 64;
+
+// Everything the scoring / selection / compaction kernels need besides the
+// descriptors.  Passed by value.
+struct LaunchParams {
+  const finch_problem* probs;  // device descriptors
+  int32_t n_problems;
+  int32_t group;               // G
+  int32_t tiles_max;           // ceil(max_p (c+m) / kTileKeys)
+  int32_t rpad_max;            // max_p round_up(G*n_que, 32)
+  int32_t row_chunk;           // rows staged per pass over the keys (multiple of 32)
+  int32_t score_stride;        // floats per problem in ws_scores
+  float scale_log2;            // log2(e) / sqrt(d_k)
+  float2* stats;               // [P][tiles_max][rpad_max] partial (max, sum) per tile
+  float* lse;                  // [P][rpad_max] log2-domain log-sum-exp per prompt row
+  float* ws_scores;            // [P][score_stride] used when desc.scores == NULL
+};
+
+// Launchers; each returns hipGetLastError() after the launch.
+unsigned score_grid(const LaunchParams& p);
+hipError_t launch_rowstats_bf16(int head_dim, const LaunchParams& p, size_t lds, hipStream_t s);
+hipError_t launch_colsum_bf16(int head_dim, const LaunchParams& p, size_t lds, hipStream_t s);
+hipError_t launch_rowstats_f32(int head_dim, const LaunchParams& p, size_t lds, hipStream_t s);
+hipError_t launch_colsum_f32(int head_dim, const LaunchParams& p, size_t lds, hipStream_t s);
+hipError_t launch_lse(const LaunchParams& p, hipStream_t s);
+hipError_t launch_select(const LaunchParams& p, hipStream_t s);
+hipError_t launch_gather(const LaunchParams& p, int row_bytes, int r_max, hipStream_t s);
+// Raise the dynamic-LDS limit of the scoring kernels of one dtype to `bytes`.
+hipError_t set_max_lds_bf16(size_t bytes);
+hipError_t set_max_lds_f32(size_t bytes);
+
+
+// Descriptor pointers are generic; telling the compiler they are global memory
+// turns flat loads/stores into global ones (which do not tie up the LDS counter).
+#define FINCH_GLOBAL __attribute__((address_space(1)))
+template <typename T>
+__device__ __forceinline__ const FINCH_GLOBAL T* as_global(const void* p) {
+  return (const FINCH_GLOBAL T*)(p);
+}
+template <typename T>
+__device__ __forceinline__ FINCH_GLOBAL T* as_global_mut(void* p) {
+  return (FINCH_GLOBAL T*)(p);
+}
+
+}  // namespace finch

@@ -1,0 +1,75 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, it exports
+every function include/finch.h declares, and its host-only entry points behave."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+import paper_2408_00167_amd as F
+from oracle import finch_oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    with open(os.path.join(ROOT, "include", "finch.h")) as f:
+        text = re.sub(r"/\*.*?\*/", "", f.read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(finch_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function():
+    lib = F.load_library()
+    names = declared_functions()
+    assert set(names) == set(F.EXPORTED_SYMBOLS)
+    for name in names:
+        assert getattr(lib, name) is not None
+    assert F.finch_version() >= 100
+
+
+def test_problem_struct_layout_matches_header():
+    assert ctypes.sizeof(F.finch_problem) == 88
+    assert F.finch_problem.n_que.offset == 72 and F.finch_problem.r.offset == 84
+    assert ctypes.sizeof(F.finch_config) == 16
+
+
+def test_schedule_matches_paper_rule_and_oracle():
+    assert F.finch_schedule(1024, 256, 64) == [16, 32, 48, 64]
+    assert F.finch_schedule(131072, 4096, 1408) == [44 * i for i in range(1, 33)]
+    for n_cont, m, k in [(1000, 256, 100), (2049, 2048, 64), (5, 8, 2), (4096, 512, 5000),
+                         (777, 100, 777), (65536, 2048, 2048), (3000, 7, 1), (40000, 2048, 1250),
+                         (1 << 33, 1 << 20, 12345)]:
+        assert F.finch_schedule(n_cont, m, k) == O.schedule(n_cont, m, k)
+    assert F.finch_schedule(0, 16, 4) == []
+
+
+def test_schedule_argument_errors():
+    lib = F.load_library()
+    buf = (ctypes.c_int32 * 4)()
+    assert lib.finch_schedule(100, 0, 10, buf, 4) == F.FINCH_ERR_INVALID_ARG
+    assert lib.finch_schedule(-1, 8, 10, buf, 4) == F.FINCH_ERR_INVALID_ARG
+    assert lib.finch_schedule(100, 8, 10, buf, 4) == F.FINCH_ERR_CAPACITY      # needs 13 slots
+    assert lib.finch_schedule(100, 50, 10, None, 4) == F.FINCH_ERR_INVALID_ARG
+    assert lib.finch_status_string(F.FINCH_ERR_WORKSPACE).decode().startswith("workspace")
+
+
+def test_create_rejects_bad_configs_before_touching_the_gpu():
+    lib = F.load_library()
+    ctx = ctypes.c_void_p()
+    for cfg, want in [(F.finch_config(2, 128, 1, 0), F.FINCH_ERR_UNSUPPORTED),
+                      (F.finch_config(F.FINCH_BF16, 96, 1, 0), F.FINCH_ERR_UNSUPPORTED),
+                      (F.finch_config(F.FINCH_BF16, 128, 0, 0), F.FINCH_ERR_UNSUPPORTED),
+                      (F.finch_config(F.FINCH_BF16, 128, 4, 7), F.FINCH_ERR_INVALID_ARG)]:
+        assert lib.finch_create(ctypes.byref(cfg), ctypes.byref(ctx)) == want
+        assert not ctx.value
+    assert lib.finch_create(None, ctypes.byref(ctx)) == F.FINCH_ERR_INVALID_ARG
+
+
+@pytest.mark.skipif(torch.cuda.is_available(), reason="only meaningful without a GPU")
+def test_no_gpu_means_loud_failure_not_fallback():
+    with pytest.raises(RuntimeError):
+        F.Finch(F.FINCH_BF16, 128, 4)
+    with pytest.raises(F.FinchError) as e:
+        F.finch_create(F.FINCH_BF16, 128, 4)
+    assert e.value.status == F.FINCH_ERR_HIP
