@@ -33,7 +33,9 @@ __global__ __launch_bounds__(256) void gather_rows(LaunchParams prm, int blocks_
 #pragma unroll
   for (int it = 0; it < kIters; ++it) {
     const int t = min(row0 + it * kRowsPerIter + sub, r - 1);
-    const int j = as_global<int32_t>(pb.idx)[t];
+    // idx normally comes from the selection kernel; clamp so that a caller-supplied
+    // index can never read outside the candidates
+    const int j = min(max(as_global<int32_t>(pb.idx)[t], 0), N - 1);
     const bool cached = j < pb.c;
     const size_t off = static_cast<size_t>(cached ? j : j - pb.c) * SEGS + seg;
     kv[it] = (cached ? kc : kk)[off];
