@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the Finch selection path (score + top-r + compact over the whole
+chunk loop) on one MI355X.
+
+One bench "step" = one full pass of the hot path over one batch: every chunk step
+of every problem of the workload (C4 by default: 256 problems x 32 chunk steps,
+131072 document tokens).  Inputs are synthetic and already resident in HBM when
+the timed region starts.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(w, loop):
+    """Bytes the method must move, per kernel class and in total, summed over one
+    full chunk loop: every candidate key read once for scoring, Q once per step,
+    every kept K and V row read once and written once."""
+    e, d = w.elem_bytes, w.head_dim
+    per = dict(score_pass=0, select=0, gather=0)
+    keys = 0
+    for i in range(loop.n_steps):
+        for p, (c, m, r) in zip(loop.active[i], loop.step_shapes[i]):
+            R = w.group * loop.problems[p]["n_que"]
+            N = c + m
+            keys += N
+            per["score_pass"] += N * d * e + R * d * e
+            per["select"] += 4 * N + 4 * min(r, N)
+            per["gather"] += min(r, N) * d * e * 4
+    total = per["score_pass"] + per["gather"]
+    return per, total, keys
+
+
+def cpu_baseline(w, probs_cpu, chunk, budget_s=20.0):
+    """The oracle, as it stands, on the host cores: whole chunk loops of a few
+    sampled problems, extrapolated linearly to the whole job."""
+    from oracle import finch_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([int(x.get("num_threads", 1)) for x in threadpool_info()] + [1])
+    except Exception:
+        cores = 1
+    done, t0 = 0, time.perf_counter()
+    for pb in probs_cpu:
+        O.compress(pb["Q"], pb["K"], pb["V"], chunk, pb["budget"])
+        done += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    n_tokens = sum(r.n_cont for r in w.requests)
+    whole_job_s = dt / done * w.n_problems
+    return dict(value=n_tokens / whole_job_s, unit="document tokens/s", cores=cores, kind="oracle",
+                sample=(f"{done} of {w.n_problems} problems of {w.name} (request 0, layer 0), full "
+                        f"chunk loop each, {dt:.1f} s measured, extrapolated linearly to all problems"))
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C4")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (problems are independent; there is no "
+              "multi-GPU path to measure). Re-run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2408_00167_amd as F
+    import workloads as W
+    from paper_2408_00167_amd.driver import ChunkLoop
+
+    if not os.path.exists(F.LIB_PATH):
+        from paper_2408_00167_amd.build import build_library
+        build_library(verbose=False)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU path", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    w = W.get_workload(args.workload)
+    fin = F.Finch(F.FINCH_BF16 if w.dtype == "bf16" else F.FINCH_F32, w.head_dim, w.group, device=dev)
+
+    t_gen = time.perf_counter()
+    probs = []
+    for b, l, g in W.problems_of(w):
+        p = W.make_problem(w, b, l, g, device=dev)
+        probs.append(dict(Q=p["Q"], K=p["K"], V=p["V"], n_que=w.requests[b].n_que,
+                          budget=w.requests[b].budget))
+    loop = ChunkLoop(fin, probs, w.chunk, history=False, want_scores=False)
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+    per_kernel_bytes, total_bytes, keys = algorithmic_bytes(w, loop)
+    n_tokens = sum(r.n_cont for r in w.requests)
+
+    for _ in range(args.warmup):
+        loop.run()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        loop.run()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ev_ms = ev0.elapsed_time(ev1) / args.steps
+    ms = wall_ms
+
+    # Per-kernel durations: the same loop again with HIP events around every launch
+    # (on the launch stream).  Kept out of the pass that produced `value` because the
+    # event records themselves lengthen the loop.
+    roofline, kernels = None, None
+    if not args.no_profile:
+        F.finch_profile(fin.ctx, True)
+        prof_steps = min(args.steps, max(1, 8192 // max(1, 5 * loop.n_steps)))
+        torch.cuda.synchronize()
+        tp = time.perf_counter()
+        for _ in range(prof_steps):
+            loop.run()
+        torch.cuda.synchronize()
+        prof_ms = (time.perf_counter() - tp) * 1e3 / prof_steps
+        prof = F.finch_profile_read(fin.ctx)
+        F.finch_profile(fin.ctx, False)
+        kernels = {}
+        for name, v in prof.items():
+            if v["launches"]:
+                kernels[name] = dict(avg_us=1e3 * v["ms"] / v["launches"], launches_per_step=v["launches"] // prof_steps,
+                                     ms_per_step=v["ms"] / prof_steps)
+        dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+        klass = {"rowstats": "score_pass", "colsum": "score_pass", "select": "select",
+                 "gather": "gather", "lse": "select"}[dom]
+        launches = kernels[dom]["launches_per_step"]
+        bytes_per_launch = per_kernel_bytes[klass] / launches
+        achieved = bytes_per_launch / (kernels[dom]["avg_us"] * 1e-6) / 1e9
+        roofline = dict(bound="hbm", kernel=dom, achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s",
+                        frac=achieved / HBM_PEAK_GBPS, traffic=None,
+                        bytes_per_launch=bytes_per_launch, avg_launch_us=kernels[dom]["avg_us"],
+                        launches_per_step=launches, profiled_ms_per_step=prof_ms)
+
+    path_gbps = total_bytes / (ms * 1e-3) / 1e9
+    out = {
+        "metric": "document tokens compressed/sec (score+topk+compact); achieved HBM GB/s",
+        "value": n_tokens / (ms * 1e-3),
+        "unit": "document tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "event_ms_per_step": ev_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.note}", "problems": w.n_problems,
+                   "document_tokens": n_tokens, "chunk": w.chunk, "chunk_steps": loop.n_steps,
+                   "head_dim": w.head_dim, "group": w.group,
+                   "prompt_rows": [w.rows(r) for r in w.requests][:4],
+                   "budget": [r.budget for r in w.requests][:4], "keys_scored": keys},
+        "path": {"algorithmic_bytes": total_bytes, "achieved_GBps": path_gbps,
+                 "frac_of_hbm_peak": path_gbps / HBM_PEAK_GBPS},
+        "kernels": kernels,
+        "roofline": roofline,
+        "setup_s": t_gen,
+    }
+    if not args.no_cpu_baseline:
+        sample = []
+        b0 = 0
+        for g in range(min(w.kv_heads, 8)):
+            p = W.make_problem(w, b0, 0, g, device=dev)
+            sample.append(dict(Q=W.to_numpy_storage(p["Q"]), K=W.to_numpy_storage(p["K"]),
+                               V=W.to_numpy_storage(p["V"]), budget=w.requests[b0].budget))
+        out["cpu_baseline"] = cpu_baseline(w, sample, w.chunk)
+    print(json.dumps(out), flush=True)
+    fin.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

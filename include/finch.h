@@ -117,6 +117,25 @@ finch_status finch_step(finch_ctx* ctx, const finch_problem* host_desc,
 finch_status finch_schedule(int64_t n_cont, int32_t m, int64_t k, int32_t* r_out,
                             int32_t r_len);
 
+/* Measurement helpers (not part of the method).  finch_profile(ctx, 1) creates a
+ * pool of HIP events (this call allocates; make it outside any timed loop) and
+ * from then on every kernel launch of this context is bracketed by two events on
+ * the launch stream; finch_profile(ctx, 0) stops and frees them.
+ * finch_profile_read waits for the recorded events, adds up the elapsed
+ * milliseconds and launch counts per kernel class into ms[FINCH_KERNEL_COUNT] and
+ * launches[FINCH_KERNEL_COUNT] (host arrays), and clears the pool.  At most 8192
+ * launches are recorded between two reads; later ones are not timed. */
+typedef enum {
+  FINCH_KERNEL_ROWSTATS = 0, /* scoring pass 1: per-row softmax statistics   */
+  FINCH_KERNEL_LSE = 1,      /* merge of the per-tile statistics             */
+  FINCH_KERNEL_COLSUM = 2,   /* scoring pass 2: per-key sums of the weights  */
+  FINCH_KERNEL_SELECT = 3,   /* top-r                                        */
+  FINCH_KERNEL_GATHER = 4,   /* compaction                                   */
+  FINCH_KERNEL_COUNT = 5
+} finch_kernel;
+finch_status finch_profile(finch_ctx* ctx, int32_t enable);
+finch_status finch_profile_read(finch_ctx* ctx, float* ms, int32_t* launches);
+
 /* The hipError_t (as int) of the last failed HIP call seen by this context. */
 int32_t finch_last_hip_error(const finch_ctx* ctx);
 const char* finch_status_string(finch_status s);

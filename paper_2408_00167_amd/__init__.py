@@ -29,8 +29,10 @@ FINCH_BF16 = 1
 EXPORTED_SYMBOLS = (
     "finch_create", "finch_destroy", "finch_workspace_size", "finch_score", "finch_topk",
     "finch_compact", "finch_step", "finch_schedule", "finch_last_hip_error",
-    "finch_status_string", "finch_version",
+    "finch_status_string", "finch_version", "finch_profile", "finch_profile_read",
 )
+
+KERNEL_NAMES = ("rowstats", "lse", "colsum", "select", "gather")
 
 
 class FinchError(RuntimeError):
@@ -84,6 +86,10 @@ def load_library() -> ctypes.CDLL:
     lib.finch_last_hip_error.restype = i32
     lib.finch_status_string.argtypes = [ctypes.c_int]
     lib.finch_status_string.restype = ctypes.c_char_p
+    lib.finch_profile.argtypes = [vp, i32]
+    lib.finch_profile.restype = ctypes.c_int
+    lib.finch_profile_read.argtypes = [vp, P(ctypes.c_float), P(i32)]
+    lib.finch_profile_read.restype = ctypes.c_int
     lib.finch_version.argtypes = []
     lib.finch_version.restype = i32
     _lib = lib
@@ -148,6 +154,18 @@ def finch_schedule(n_cont: int, m: int, k: int) -> List[int]:
     buf = (ctypes.c_int32 * max(1, steps))()
     _check(load_library().finch_schedule(n_cont, m, k, buf, steps), "finch_schedule")
     return list(buf[:steps])
+
+
+def finch_profile(ctx, enable: bool) -> None:
+    _check(load_library().finch_profile(ctx, 1 if enable else 0), "finch_profile", ctx)
+
+
+def finch_profile_read(ctx) -> Dict[str, Dict[str, float]]:
+    n = len(KERNEL_NAMES)
+    ms = (ctypes.c_float * n)()
+    cnt = (ctypes.c_int32 * n)()
+    _check(load_library().finch_profile_read(ctx, ms, cnt), "finch_profile_read", ctx)
+    return {KERNEL_NAMES[i]: {"ms": float(ms[i]), "launches": int(cnt[i])} for i in range(n)}
 
 
 def finch_version() -> int:

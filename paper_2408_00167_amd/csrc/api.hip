@@ -14,6 +14,11 @@ struct finch_ctx {
   size_t max_lds;   // largest dynamic LDS a workgroup may ask for
   int last_hip;     // hipError_t of the last failed HIP call
   int row_bytes;    // bytes of one K or V row
+  // optional per-kernel timing (finch_profile): pairs of events around launches
+  bool prof_on;
+  int prof_used;
+  hipEvent_t* prof_ev;   // 2 * kProfPairs events, or nullptr
+  int* prof_kind;        // kernel class of each pair
 };
 
 namespace {
@@ -174,25 +179,67 @@ finch_status hip_fail(finch_ctx* ctx, hipError_t e) {
   return FINCH_ERR_HIP;
 }
 
+constexpr int kProfPairs = 8192;
+
+// Brackets one kernel launch with two events on the launch stream when profiling
+// is on; does nothing otherwise.
+struct ProfScope {
+  finch_ctx* ctx;
+  hipStream_t s;
+  int slot;
+  ProfScope(finch_ctx* c, int kind, hipStream_t st) : ctx(c), s(st), slot(-1) {
+    if (c->prof_on && c->prof_used < kProfPairs) {
+      slot = c->prof_used++;
+      c->prof_kind[slot] = kind;
+      (void)hipEventRecord(c->prof_ev[2 * slot], s);
+    }
+  }
+  ~ProfScope() {
+    if (slot >= 0) (void)hipEventRecord(ctx->prof_ev[2 * slot + 1], s);
+  }
+};
+
 finch_status run_score(finch_ctx* ctx, const LaunchParams& p, const Plan& pl, hipStream_t s) {
   if (p.n_problems == 0 || pl.tiles_max == 0) return FINCH_OK;
   hipError_t e;
   const int d = ctx->cfg.head_dim;
-  if (ctx->cfg.dtype == FINCH_BF16) {
-    e = finch::launch_rowstats_bf16(d, p, pl.lds_bytes, s);
-    if (e != hipSuccess) return hip_fail(ctx, e);
+  const bool bf16 = ctx->cfg.dtype == FINCH_BF16;
+  {
+    ProfScope ps(ctx, FINCH_KERNEL_ROWSTATS, s);
+    e = bf16 ? finch::launch_rowstats_bf16(d, p, pl.lds_bytes, s)
+             : finch::launch_rowstats_f32(d, p, pl.lds_bytes, s);
+  }
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  {
+    ProfScope ps(ctx, FINCH_KERNEL_LSE, s);
     e = finch::launch_lse(p, s);
-    if (e != hipSuccess) return hip_fail(ctx, e);
-    e = finch::launch_colsum_bf16(d, p, pl.lds_bytes, s);
-  } else {
-    e = finch::launch_rowstats_f32(d, p, pl.lds_bytes, s);
-    if (e != hipSuccess) return hip_fail(ctx, e);
-    e = finch::launch_lse(p, s);
-    if (e != hipSuccess) return hip_fail(ctx, e);
-    e = finch::launch_colsum_f32(d, p, pl.lds_bytes, s);
+  }
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  {
+    ProfScope ps(ctx, FINCH_KERNEL_COLSUM, s);
+    e = bf16 ? finch::launch_colsum_bf16(d, p, pl.lds_bytes, s)
+             : finch::launch_colsum_f32(d, p, pl.lds_bytes, s);
   }
   if (e != hipSuccess) return hip_fail(ctx, e);
   return FINCH_OK;
+}
+
+finch_status run_select(finch_ctx* ctx, const LaunchParams& p, hipStream_t s) {
+  hipError_t e;
+  {
+    ProfScope ps(ctx, FINCH_KERNEL_SELECT, s);
+    e = finch::launch_select(p, s);
+  }
+  return e == hipSuccess ? FINCH_OK : hip_fail(ctx, e);
+}
+
+finch_status run_gather(finch_ctx* ctx, const LaunchParams& p, int r_max, hipStream_t s) {
+  hipError_t e;
+  {
+    ProfScope ps(ctx, FINCH_KERNEL_GATHER, s);
+    e = finch::launch_gather(p, ctx->row_bytes, r_max, s);
+  }
+  return e == hipSuccess ? FINCH_OK : hip_fail(ctx, e);
 }
 
 }  // namespace
@@ -213,6 +260,10 @@ finch_status finch_create(const finch_config* cfg, finch_ctx** out) {
   ctx->device = -1;
   ctx->max_lds = 64 * 1024;
   ctx->row_bytes = cfg->head_dim * (cfg->dtype == FINCH_BF16 ? 2 : 4);
+  ctx->prof_on = false;
+  ctx->prof_used = 0;
+  ctx->prof_ev = nullptr;
+  ctx->prof_kind = nullptr;
   hipError_t e = hipGetDevice(&ctx->device);
   if (e == hipSuccess) {
     int v = 0;
@@ -234,7 +285,52 @@ finch_status finch_create(const finch_config* cfg, finch_ctx** out) {
 }
 
 finch_status finch_destroy(finch_ctx* ctx) {
+  if (ctx) (void)finch_profile(ctx, 0);
   delete ctx;
+  return FINCH_OK;
+}
+
+finch_status finch_profile(finch_ctx* ctx, int32_t enable) {
+  if (!ctx) return FINCH_ERR_INVALID_ARG;
+  if (enable && !ctx->prof_ev) {
+    ctx->prof_ev = new (std::nothrow) hipEvent_t[2 * kProfPairs];
+    ctx->prof_kind = new (std::nothrow) int[kProfPairs];
+    if (!ctx->prof_ev || !ctx->prof_kind) return FINCH_ERR_INVALID_ARG;
+    for (int i = 0; i < 2 * kProfPairs; ++i) {
+      const hipError_t e = hipEventCreate(&ctx->prof_ev[i]);
+      if (e != hipSuccess) return hip_fail(ctx, e);
+    }
+    ctx->prof_used = 0;
+  }
+  if (!enable && ctx->prof_ev) {
+    for (int i = 0; i < 2 * kProfPairs; ++i) (void)hipEventDestroy(ctx->prof_ev[i]);
+    delete[] ctx->prof_ev;
+    delete[] ctx->prof_kind;
+    ctx->prof_ev = nullptr;
+    ctx->prof_kind = nullptr;
+    ctx->prof_used = 0;
+  }
+  ctx->prof_on = enable != 0;
+  return FINCH_OK;
+}
+
+finch_status finch_profile_read(finch_ctx* ctx, float* ms, int32_t* launches) {
+  if (!ctx || !ms || !launches) return FINCH_ERR_INVALID_ARG;
+  for (int k = 0; k < FINCH_KERNEL_COUNT; ++k) {
+    ms[k] = 0.f;
+    launches[k] = 0;
+  }
+  if (!ctx->prof_ev) return FINCH_OK;
+  for (int i = 0; i < ctx->prof_used; ++i) {
+    hipError_t e = hipEventSynchronize(ctx->prof_ev[2 * i + 1]);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    float t = 0.f;
+    e = hipEventElapsedTime(&t, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    ms[ctx->prof_kind[i]] += t;
+    launches[ctx->prof_kind[i]] += 1;
+  }
+  ctx->prof_used = 0;
   return FINCH_OK;
 }
 
@@ -273,8 +369,7 @@ finch_status finch_topk(finch_ctx* ctx, const finch_problem* host_desc,
   if ((st = check_workspace(pl, ws, ws_bytes)) != FINCH_OK) return st;
   if (n == 0 || pl.r_max == 0) return FINCH_OK;
   const LaunchParams p = make_params(ctx, dev_desc, n, pl, ws);
-  const hipError_t e = finch::launch_select(p, static_cast<hipStream_t>(stream));
-  return e == hipSuccess ? FINCH_OK : hip_fail(ctx, e);
+  return run_select(ctx, p, static_cast<hipStream_t>(stream));
 }
 
 finch_status finch_compact(finch_ctx* ctx, const finch_problem* host_desc,
@@ -288,9 +383,7 @@ finch_status finch_compact(finch_ctx* ctx, const finch_problem* host_desc,
   if ((st = check_workspace(pl, ws, ws_bytes)) != FINCH_OK) return st;
   if (n == 0 || pl.r_max == 0) return FINCH_OK;
   const LaunchParams p = make_params(ctx, dev_desc, n, pl, ws);
-  const hipError_t e =
-      finch::launch_gather(p, ctx->row_bytes, pl.r_max, static_cast<hipStream_t>(stream));
-  return e == hipSuccess ? FINCH_OK : hip_fail(ctx, e);
+  return run_gather(ctx, p, pl.r_max, static_cast<hipStream_t>(stream));
 }
 
 finch_status finch_step(finch_ctx* ctx, const finch_problem* host_desc,
@@ -307,11 +400,8 @@ finch_status finch_step(finch_ctx* ctx, const finch_problem* host_desc,
   hipStream_t s = static_cast<hipStream_t>(stream);
   if ((st = run_score(ctx, p, pl, s)) != FINCH_OK) return st;
   if (pl.r_max == 0) return FINCH_OK;
-  hipError_t e = finch::launch_select(p, s);
-  if (e != hipSuccess) return hip_fail(ctx, e);
-  e = finch::launch_gather(p, ctx->row_bytes, pl.r_max, s);
-  if (e != hipSuccess) return hip_fail(ctx, e);
-  return FINCH_OK;
+  if ((st = run_select(ctx, p, s)) != FINCH_OK) return st;
+  return run_gather(ctx, p, pl.r_max, s);
 }
 
 finch_status finch_schedule(int64_t n_cont, int32_t m, int64_t k, int32_t* r_out, int32_t r_len) {

@@ -1,0 +1,95 @@
+"""Parity at the workloads' full sizes, in the launch configuration bench.py times:
+all problems of a workload in one batch per chunk step.  A seeded sample of
+problems is validated step by step against the oracle; every problem is checked
+through properties that hold at any size (scores of a step sum to R, indices
+ascending and in range, final cache rows bitwise equal to the document rows at
+the positions composed from the index history)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2408_00167_amd as F
+import workloads as W
+from paper_2408_00167_amd.driver import ChunkLoop
+from tests import gpu_harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def run_full(name, n_sample, seed):
+    w = W.get_workload(name)
+    fin = F.Finch(F.FINCH_BF16 if w.dtype == "bf16" else F.FINCH_F32, w.head_dim, w.group)
+    triples = list(W.problems_of(w))
+    say(f"{name}: drawing {len(triples)} problems on the GPU")
+    probs = [H.make_gpu_problem(w, b, l, g) for b, l, g in triples]
+    loop = ChunkLoop(fin, probs, w.chunk, history=True)
+    say(f"{name}: {loop.n_steps} chunk steps")
+    loop.run()
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(seed)
+    sample = sorted(rng.choice(len(probs), size=min(n_sample, len(probs)), replace=False).tolist())
+    say(f"{name}: validating problems {sample} against the oracle")
+    st = H.validate_chunk_loop(loop, sample, name)
+    say(f"{name}: sample ok {st}")
+    # properties over every problem (flags stay on the device; one readback each)
+    for p, pb in enumerate(probs):
+        R = w.group * pb["n_que"]
+        pos = torch.zeros(0, dtype=torch.long, device="cuda")
+        flags = []
+        for i, r in enumerate(loop.rs[p]):
+            lo, hi = i * loop.chunk, min((i + 1) * loop.chunk, loop.n_cont[p])
+            scores, idx = loop.step_outputs(i, p)
+            idx = idx.long()
+            if i in (0, len(loop.rs[p]) - 1):
+                flags.append(((scores.double().sum() - R).abs() < 1e-3 * R).reshape(1))
+            n = pos.numel() + (hi - lo)
+            assert idx.numel() == min(r, n)
+            if idx.numel():
+                flags.append(((idx.min() >= 0) & (idx.max() < n)).reshape(1))
+                flags.append((idx[1:] > idx[:-1]).all().reshape(1))
+                idx = idx.clamp(0, n - 1)
+            pos = torch.cat([pos, torch.arange(lo, hi, device="cuda")])[idx]
+        Kt, Vt = loop.final_cache(p)
+        flags.append((Kt == pb["K"][pos]).all().reshape(1))
+        flags.append((Vt == pb["V"][pos]).all().reshape(1))
+        assert bool(torch.cat(flags).all()), (name, p, torch.cat(flags).tolist())
+    say(f"{name}: all {len(probs)} problems pass the size-independent properties")
+    # planted keys: a soft check of the recipe, not an invariant of the method
+    if w.planted_frac or w.planted_count:
+        recall = []
+        for p in sample:
+            pb = probs[p]
+            Kt, _ = loop.final_cache(p)
+            planted = pb["K"][pb["planted"]]
+            k_kept = min(loop.rs[p][-1], planted.shape[0])
+            hits = int((Kt[:, None, :8] == planted[None, :1, :8]).all(dim=2).any(dim=1).sum())
+            recall.append(hits / max(1, k_kept))
+        say(f"{name}: planted-key recall on the sample {np.round(recall, 3).tolist()}")
+    fin.close()
+    del loop, probs
+    torch.cuda.empty_cache()
+    return st
+
+
+@pytest.mark.timeout(600)
+def test_c2_full_size():
+    run_full("C2", 6, seed=2)
+
+
+@pytest.mark.timeout(600)
+def test_c3_full_size():
+    run_full("C3", 4, seed=3)
+
+
+@pytest.mark.timeout(900)
+def test_c4_full_size():
+    run_full("C4", 4, seed=4)
+
+
+@pytest.mark.timeout(1200)
+def test_c5_full_size():
+    run_full("C5", 3, seed=5)
