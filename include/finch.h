@@ -117,6 +117,25 @@ finch_status finch_step(finch_ctx* ctx, const finch_problem* host_desc,
 finch_status finch_schedule(int64_t n_cont, int32_t m, int64_t k, int32_t* r_out,
                             int32_t r_len);
 
+/* Options.  FINCH_OPT_SCORING_PATH picks the scoring kernels: AUTO (default) uses
+ * the single-pass kernel, in which the workgroups of one problem exchange their
+ * softmax row statistics while their tiles stay in registers, whenever the batch
+ * allows it (bf16, G*n_que <= 256, the device can hold all tiles of eight
+ * problems at once) and the two-pass kernels otherwise; TWO_PASS and FUSED force
+ * one of them (FUSED makes unsupported batches fail with FINCH_ERR_UNSUPPORTED).
+ * FINCH_OPT_SPIN_LIMIT bounds how often a workgroup of the single-pass kernel
+ * polls for the other tiles of its problem before it gives up, raises the
+ * context's device error word and carries on (the launch always terminates).
+ * One context must not run on two streams at the same time. */
+typedef enum { FINCH_OPT_SCORING_PATH = 1, FINCH_OPT_SPIN_LIMIT = 2 } finch_option;
+typedef enum { FINCH_SCORING_AUTO = 0, FINCH_SCORING_TWO_PASS = 1, FINCH_SCORING_FUSED = 2 } finch_scoring;
+finch_status finch_set_option(finch_ctx* ctx, int32_t option, int64_t value);
+
+/* Synchronises `stream`, then reports the context's device error word in
+ * *device_error (0 = none; bit 0 = a bounded wait was abandoned and the scores of
+ * that launch are invalid) and clears it.  The only call that blocks. */
+finch_status finch_check(finch_ctx* ctx, void* stream, int32_t* device_error);
+
 /* Measurement helpers (not part of the method).  finch_profile(ctx, 1) creates a
  * pool of HIP events (this call allocates; make it outside any timed loop) and
  * from then on every kernel launch of this context is bracketed by two events on
@@ -131,7 +150,8 @@ typedef enum {
   FINCH_KERNEL_COLSUM = 2,   /* scoring pass 2: per-key sums of the weights  */
   FINCH_KERNEL_SELECT = 3,   /* top-r                                        */
   FINCH_KERNEL_GATHER = 4,   /* compaction                                   */
-  FINCH_KERNEL_COUNT = 5
+  FINCH_KERNEL_FUSED_SCORE = 5, /* single-pass scoring (replaces 0..2)       */
+  FINCH_KERNEL_COUNT = 6
 } finch_kernel;
 finch_status finch_profile(finch_ctx* ctx, int32_t enable);
 finch_status finch_profile_read(finch_ctx* ctx, float* ms, int32_t* launches);

@@ -30,9 +30,16 @@ EXPORTED_SYMBOLS = (
     "finch_create", "finch_destroy", "finch_workspace_size", "finch_score", "finch_topk",
     "finch_compact", "finch_step", "finch_schedule", "finch_last_hip_error",
     "finch_status_string", "finch_version", "finch_profile", "finch_profile_read",
+    "finch_set_option", "finch_check",
 )
 
-KERNEL_NAMES = ("rowstats", "lse", "colsum", "select", "gather")
+KERNEL_NAMES = ("rowstats", "lse", "colsum", "select", "gather", "fused_score")
+
+FINCH_OPT_SCORING_PATH = 1
+FINCH_OPT_SPIN_LIMIT = 2
+FINCH_SCORING_AUTO = 0
+FINCH_SCORING_TWO_PASS = 1
+FINCH_SCORING_FUSED = 2
 
 
 class FinchError(RuntimeError):
@@ -90,6 +97,10 @@ def load_library() -> ctypes.CDLL:
     lib.finch_profile.restype = ctypes.c_int
     lib.finch_profile_read.argtypes = [vp, P(ctypes.c_float), P(i32)]
     lib.finch_profile_read.restype = ctypes.c_int
+    lib.finch_set_option.argtypes = [vp, i32, i64]
+    lib.finch_set_option.restype = ctypes.c_int
+    lib.finch_check.argtypes = [vp, vp, P(i32)]
+    lib.finch_check.restype = ctypes.c_int
     lib.finch_version.argtypes = []
     lib.finch_version.restype = i32
     _lib = lib
@@ -168,6 +179,18 @@ def finch_profile_read(ctx) -> Dict[str, Dict[str, float]]:
     return {KERNEL_NAMES[i]: {"ms": float(ms[i]), "launches": int(cnt[i])} for i in range(n)}
 
 
+def finch_set_option(ctx, option: int, value: int) -> None:
+    _check(load_library().finch_set_option(ctx, option, value), "finch_set_option", ctx)
+
+
+def finch_check(ctx, stream: int = 0) -> int:
+    """Synchronise the stream and return (and clear) the device error word."""
+    out = ctypes.c_int32(0)
+    _check(load_library().finch_check(ctx, ctypes.c_void_p(stream), ctypes.byref(out)),
+           "finch_check", ctx)
+    return out.value
+
+
 def finch_version() -> int:
     return load_library().finch_version()
 
@@ -229,6 +252,14 @@ class Finch:
             self.close()
         except Exception:
             pass
+
+    def set_scoring_path(self, path: int) -> None:
+        finch_set_option(self.ctx, FINCH_OPT_SCORING_PATH, path)
+
+    def check(self, stream=None) -> int:
+        import torch
+        s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
+        return finch_check(self.ctx, s)
 
     def reserve(self, batch: Batch) -> int:
         import torch

@@ -13,7 +13,8 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 LIB_PATH = os.path.join(PKG_DIR, "libfinch.so")
 
-SOURCES = ["api.hip", "score_bf16.hip", "score_f32.hip", "select.hip", "gather.hip"]
+SOURCES = ["api.hip", "score_bf16.hip", "score_fused.hip", "score_f32.hip", "select.hip",
+           "gather.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

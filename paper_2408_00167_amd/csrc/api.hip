@@ -3,6 +3,7 @@
 // finch_create.
 #include <cmath>
 #include <cstdint>
+#include <cstdio>
 #include <cstring>
 #include <new>
 
@@ -19,6 +20,13 @@ struct finch_ctx {
   int prof_used;
   hipEvent_t* prof_ev;   // 2 * kProfPairs events, or nullptr
   int* prof_kind;        // kernel class of each pair
+  // fused scoring
+  unsigned* sync;        // device, finch::kSyncWords words, zero between launches
+  int n_cu;              // compute units of the device
+  int scoring_path;      // FINCH_SCORING_AUTO / _TWO_PASS / _FUSED
+  uint32_t spin_limit;
+  int fused_blocks[2][5];  // cached occupancy per (head_dim index, nq); 0 = not asked yet
+  size_t fused_blocks_lds[2][5];
 };
 
 namespace {
@@ -35,6 +43,9 @@ enum Need : unsigned {
 struct Plan {
   int32_t n_max = 0, rows_max = 0, rpad_max = 0, r_max = 0, tiles_max = 0, row_chunk = 32;
   int32_t score_stride = 0;
+  int32_t tiles_fused = 0, fused_nq = 0;
+  bool fused_shape_ok = false;   // shapes allow the fused kernel (occupancy checked at launch)
+  size_t fused_lds = 0;
   size_t lds_bytes = 0;
   size_t off_stats = 0, off_lse = 0, off_scores = 0, total = 0;
 };
@@ -87,9 +98,17 @@ finch_status make_plan(const finch_ctx* ctx, const finch_problem* hd, int32_t n,
   if (pg * (pl.tiles_max > 0 ? pl.tiles_max : 1) >= (int64_t{1} << 31)) return FINCH_ERR_CAPACITY;
   const int64_t gb = (static_cast<int64_t>(pl.r_max) + finch::kGatherRows - 1) / finch::kGatherRows;
   if (gb * n >= (int64_t{1} << 31)) return FINCH_ERR_CAPACITY;
+  pl.tiles_fused = static_cast<int32_t>((n_max + finch::kFusedKeys - 1) / finch::kFusedKeys);
+  pl.fused_nq = (pl.rpad_max + 63) / 64;
+  pl.fused_lds = finch::fused_lds_bytes(ctx->cfg.head_dim, pl.rpad_max);
+  pl.fused_shape_ok = ctx->cfg.dtype == FINCH_BF16 && pl.rpad_max >= 32 &&
+                      pl.rpad_max <= finch::kFusedMaxRows && n <= finch::kSyncMaxProblems &&
+                      pl.fused_lds + finch::kFusedStaticLds <= ctx->max_lds &&
+                      pg * (pl.tiles_fused > 0 ? pl.tiles_fused : 1) < (int64_t{1} << 31);
   size_t off = 0;
   pl.off_stats = off;
-  off = align_up(off + static_cast<size_t>(n) * pl.tiles_max * pl.rpad_max * sizeof(float2), 256);
+  // sized for whichever scoring kernel runs: the fused one has twice the tiles
+  off = align_up(off + static_cast<size_t>(n) * pl.tiles_fused * pl.rpad_max * sizeof(float2), 256);
   pl.off_lse = off;
   off = align_up(off + static_cast<size_t>(n) * pl.rpad_max * sizeof(float), 256);
   pl.off_scores = off;
@@ -171,7 +190,30 @@ LaunchParams make_params(const finch_ctx* ctx, const finch_problem* dd, int32_t 
   p.stats = reinterpret_cast<float2*>(base + pl.off_stats);
   p.lse = reinterpret_cast<float*>(base + pl.off_lse);
   p.ws_scores = reinterpret_cast<float*>(base + pl.off_scores);
+  p.tiles_fused = pl.tiles_fused;
+  p.spin_limit = ctx->spin_limit;
+  p.sync = ctx->sync;
   return p;
+}
+
+// Whether this batch may use the fused kernel: its shapes fit, and the device
+// holds enough workgroups at once for the waits to be safe (see score_fused.hip).
+bool use_fused(finch_ctx* ctx, const Plan& pl) {
+  if (ctx->scoring_path == FINCH_SCORING_TWO_PASS || !pl.fused_shape_ok || !ctx->sync) return false;
+  const int di = ctx->cfg.head_dim == 128 ? 1 : 0;
+  if (ctx->fused_blocks[di][pl.fused_nq] == 0 || ctx->fused_blocks_lds[di][pl.fused_nq] != pl.fused_lds) {
+    int b = 0;
+    if (finch::fused_blocks_per_cu(ctx->cfg.head_dim, pl.fused_nq, pl.fused_lds, &b) != hipSuccess) {
+      (void)hipGetLastError();
+      b = -1;
+    }
+    ctx->fused_blocks[di][pl.fused_nq] = b > 0 ? b : -1;
+    ctx->fused_blocks_lds[di][pl.fused_nq] = pl.fused_lds;
+  }
+  const int blocks = ctx->fused_blocks[di][pl.fused_nq];
+  if (blocks <= 0) return false;
+  const int64_t resident = static_cast<int64_t>(blocks) * ctx->n_cu;
+  return 8 * static_cast<int64_t>(pl.tiles_fused) <= resident;
 }
 
 finch_status hip_fail(finch_ctx* ctx, hipError_t e) {
@@ -201,9 +243,17 @@ struct ProfScope {
 
 finch_status run_score(finch_ctx* ctx, const LaunchParams& p, const Plan& pl, hipStream_t s) {
   if (p.n_problems == 0 || pl.tiles_max == 0) return FINCH_OK;
-  hipError_t e;
+  hipError_t e = hipSuccess;
   const int d = ctx->cfg.head_dim;
   const bool bf16 = ctx->cfg.dtype == FINCH_BF16;
+  if (use_fused(ctx, pl)) {
+    {
+      ProfScope ps(ctx, FINCH_KERNEL_FUSED_SCORE, s);
+      e = finch::launch_fused_bf16(d, pl.fused_nq, p, pl.fused_lds, s);
+    }
+    return e == hipSuccess ? FINCH_OK : hip_fail(ctx, e);
+  }
+  if (ctx->scoring_path == FINCH_SCORING_FUSED) return FINCH_ERR_UNSUPPORTED;
   {
     ProfScope ps(ctx, FINCH_KERNEL_ROWSTATS, s);
     e = bf16 ? finch::launch_rowstats_bf16(d, p, pl.lds_bytes, s)
@@ -264,6 +314,12 @@ finch_status finch_create(const finch_config* cfg, finch_ctx** out) {
   ctx->prof_used = 0;
   ctx->prof_ev = nullptr;
   ctx->prof_kind = nullptr;
+  ctx->sync = nullptr;
+  ctx->n_cu = 0;
+  ctx->scoring_path = FINCH_SCORING_AUTO;
+  ctx->spin_limit = 200000;
+  std::memset(ctx->fused_blocks, 0, sizeof(ctx->fused_blocks));
+  std::memset(ctx->fused_blocks_lds, 0, sizeof(ctx->fused_blocks_lds));
   hipError_t e = hipGetDevice(&ctx->device);
   if (e == hipSuccess) {
     int v = 0;
@@ -271,12 +327,24 @@ finch_status finch_create(const finch_config* cfg, finch_ctx** out) {
     if (e == hipSuccess && v > 0) ctx->max_lds = static_cast<size_t>(v);
   }
   if (e == hipSuccess) {
+    e = hipDeviceGetAttribute(&ctx->n_cu, hipDeviceAttributeMultiprocessorCount, ctx->device);
+  }
+  if (e == hipSuccess) {
     e = cfg->dtype == FINCH_BF16 ? finch::set_max_lds_bf16(ctx->max_lds)
                                  : finch::set_max_lds_f32(ctx->max_lds);
   }
+  if (e == hipSuccess && cfg->dtype == FINCH_BF16) {
+    // the fused kernel also has a few bytes of static LDS
+    e = finch::set_max_lds_fused(ctx->max_lds - finch::kFusedStaticLds);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->sync), finch::kSyncWords * sizeof(unsigned));
+    if (e == hipSuccess) e = hipMemset(ctx->sync, 0, finch::kSyncWords * sizeof(unsigned));
+  }
   if (e != hipSuccess) {
     // No usable GPU: there is no fallback path.  Report and hand nothing out.
+    std::fprintf(stderr, "finch_create: HIP error %d (%s)\n", static_cast<int>(e),
+                 hipGetErrorString(e));
     (void)hipGetLastError();
+    if (ctx->sync) (void)hipFree(ctx->sync);
     delete ctx;
     return FINCH_ERR_HIP;
   }
@@ -285,8 +353,47 @@ finch_status finch_create(const finch_config* cfg, finch_ctx** out) {
 }
 
 finch_status finch_destroy(finch_ctx* ctx) {
-  if (ctx) (void)finch_profile(ctx, 0);
+  if (ctx) {
+    (void)finch_profile(ctx, 0);
+    if (ctx->sync) (void)hipFree(ctx->sync);
+  }
   delete ctx;
+  return FINCH_OK;
+}
+
+finch_status finch_set_option(finch_ctx* ctx, int32_t option, int64_t value) {
+  if (!ctx) return FINCH_ERR_INVALID_ARG;
+  switch (option) {
+    case FINCH_OPT_SCORING_PATH:
+      if (value != FINCH_SCORING_AUTO && value != FINCH_SCORING_TWO_PASS &&
+          value != FINCH_SCORING_FUSED)
+        return FINCH_ERR_INVALID_ARG;
+      ctx->scoring_path = static_cast<int>(value);
+      return FINCH_OK;
+    case FINCH_OPT_SPIN_LIMIT:
+      if (value < 1 || value > 0x7fffffff) return FINCH_ERR_INVALID_ARG;
+      ctx->spin_limit = static_cast<uint32_t>(value);
+      return FINCH_OK;
+    default:
+      return FINCH_ERR_INVALID_ARG;
+  }
+}
+
+finch_status finch_check(finch_ctx* ctx, void* stream, int32_t* device_error) {
+  if (!ctx || !device_error) return FINCH_ERR_INVALID_ARG;
+  *device_error = 0;
+  hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  if (!ctx->sync) return FINCH_OK;
+  unsigned word = 0;
+  e = hipMemcpy(&word, ctx->sync + finch::kSyncError, sizeof(word), hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  *device_error = static_cast<int32_t>(word);
+  if (word != 0) {
+    // a wait was abandoned: counters may be stale, so clear all of them
+    e = hipMemset(ctx->sync, 0, finch::kSyncWords * sizeof(unsigned));
+    if (e != hipSuccess) return hip_fail(ctx, e);
+  }
   return FINCH_OK;
 }
 

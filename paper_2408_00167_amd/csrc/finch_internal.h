@@ -14,6 +14,19 @@ constexpr int kTileKeys = 256;
 constexpr int kMaxRowChunk = 512;
 // Rows copied by one workgroup of the compaction kernel.
 constexpr int kGatherRows = 64;
+// Fused single-pass scoring: keys per workgroup, threads per workgroup, most
+// prompt rows (padded to 32) it can keep in registers, and the layout of the
+// context-owned synchronisation words (all uint32).
+constexpr int kFusedKeys = 128;
+constexpr int kFusedThreads = 512;
+constexpr int kFusedMaxRows = 256;
+constexpr int kFusedStaticLds = 256;  // upper bound of the fused kernel's static LDS
+constexpr int kSyncTicket = 0;      // 8 ticket counters, 16 words apart
+constexpr int kSyncDone = 128;      // workgroups of the current launch that retired
+constexpr int kSyncError = 129;     // sticky error bits (bit 0: a wait ran past its limit)
+constexpr int kSyncProblems = 256;  // then per problem: {arrived, departed}
+constexpr int kSyncMaxProblems = 32768;
+constexpr int kSyncWords = kSyncProblems + 2 * kSyncMaxProblems;
 
 // Everything the scoring / selection / compaction kernels need besides the
 // descriptors.  Passed by value.
@@ -29,6 +42,12 @@ struct LaunchParams {
   float2* stats;               // [P][tiles_max][rpad_max] partial (max, sum) per tile
   float* lse;                  // [P][rpad_max] log2-domain log-sum-exp per prompt row
   float* ws_scores;            // [P][score_stride] used when desc.scores == NULL
+  // fused single-pass scoring only
+  int32_t tiles_fused;         // ceil(max_p (c+m) / kFusedKeys); stats is then
+                               // [P][tiles_fused][rpad_max]
+  uint32_t spin_limit;         // polls after which a waiting workgroup gives up
+  unsigned* sync;              // kSyncWords words owned by the context, all zero
+                               // between launches
 };
 
 // Launchers; each returns hipGetLastError() after the launch.
@@ -40,6 +59,11 @@ hipError_t launch_colsum_f32(int head_dim, const LaunchParams& p, size_t lds, hi
 hipError_t launch_lse(const LaunchParams& p, hipStream_t s);
 hipError_t launch_select(const LaunchParams& p, hipStream_t s);
 hipError_t launch_gather(const LaunchParams& p, int row_bytes, int r_max, hipStream_t s);
+unsigned fused_grid(const LaunchParams& p);
+size_t fused_lds_bytes(int head_dim, int rpad_max);
+hipError_t launch_fused_bf16(int head_dim, int nq, const LaunchParams& p, size_t lds, hipStream_t s);
+hipError_t set_max_lds_fused(size_t bytes);
+hipError_t fused_blocks_per_cu(int head_dim, int nq, size_t lds, int* blocks);
 // Raise the dynamic-LDS limit of the scoring kernels of one dtype to `bytes`.
 hipError_t set_max_lds_bf16(size_t bytes);
 hipError_t set_max_lds_f32(size_t bytes);

@@ -18,23 +18,15 @@
 //                     log2 domain; a small kernel merges tiles into lse[row].
 // Pass 2 (colsum)   : recomputes the logits and adds exp2(s - lse[row]) into the
 //                     per-key sums, i.e. the probabilities themselves in fp32.
-#include "finch_internal.h"
+#include "score_common.h"
 
 namespace finch {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
 constexpr int kWaves = 4;
 constexpr int kKB = 2;  // 32-key blocks per wave: kWaves * kKB * 32 == kTileKeys
 static_assert(kWaves * kKB * 32 == kTileKeys, "tile shape");
-
-constexpr float kInf = __builtin_inff();
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // Workgroup -> (problem, tile).  Consecutive tiles of one problem get block ids
 // that are congruent mod 8, so that under round-robin dispatch they land on one
@@ -49,117 +41,16 @@ __device__ __forceinline__ bool decode_tile(const LaunchParams& prm, int& p, int
   return p < prm.n_problems;
 }
 
-// Merge two (max, sum) pairs of a running softmax in the log2 domain.
-__device__ __forceinline__ void merge_stats(float& m, float& z, float m2, float z2) {
-  const float mm = fmaxf(m, m2);
-  if (mm == -kInf) {
-    z = 0.f;
-  } else {
-    z = z * fast_exp2(m - mm) + z2 * fast_exp2(m2 - mm);
-  }
-  m = mm;
-}
-
-// Key (row of the 32x32 logit block) held in accumulator register v of a lane in
-// lane-half h.
-__device__ __forceinline__ int acc_key(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
-
-template <int D>
-__device__ __forceinline__ void load_k_block(const finch_problem& pb, int N, int kbase, int lane,
-                                             bf16x8 (&kf)[D / 16]) {
-  const int key = kbase + (lane & 31);
-  const int h = lane >> 5;
-  if (key < N) {
-    const char* row = key < pb.c
-                          ? static_cast<const char*>(pb.k_cache) + static_cast<size_t>(key) * (D * 2)
-                          : static_cast<const char*>(pb.k_chunk) +
-                                static_cast<size_t>(key - pb.c) * (D * 2);
-    const FINCH_GLOBAL u32x4* rp = as_global<u32x4>(row);
-#pragma unroll
-    for (int s = 0; s < D / 16; ++s) {
-      const u32x4 raw = rp[2 * s + h];
-      kf[s] = __builtin_bit_cast(bf16x8, raw);
-    }
-  } else {
-    const u32x4 zero = {0u, 0u, 0u, 0u};
-#pragma unroll
-    for (int s = 0; s < D / 16; ++s) kf[s] = __builtin_bit_cast(bf16x8, zero);
-  }
-}
-
-// Copy prompt rows [row0, row0+rows) into LDS, rows past R as zeros.  Row stride
-// D*2+16 bytes keeps the 16-byte B-operand reads of 8 consecutive lanes on
-// distinct banks.
-template <int D>
-__device__ __forceinline__ void stage_q(const void* q, int R, int row0, int rows, char* lds_q,
-                                        int tid) {
-  constexpr int kSegs = D / 8;
-  constexpr int kStride = D * 2 + 16;
-  const FINCH_GLOBAL u32x4* src = as_global<u32x4>(q);
-  const int total = rows * kSegs;
-  for (int i = tid; i < total; i += kWaves * 64) {
-    const int row = i / kSegs;
-    const int seg = i - row * kSegs;
-    u32x4 val = {0u, 0u, 0u, 0u};
-    if (row0 + row < R) val = src[static_cast<size_t>(row0 + row) * kSegs + seg];
-    *reinterpret_cast<u32x4*>(lds_q + row * kStride + seg * 16) = val;
-  }
-}
-
 // logits[key][row] for the wave's key blocks against row block qb, raw dot
 // products (not yet scaled).
 template <int D>
 __device__ __forceinline__ void logits_block(const bf16x8 (&kf)[kKB][D / 16], const char* lds_q,
                                              int qb, int lane, f32x16 (&acc)[kKB]) {
-  constexpr int kStride = D * 2 + 16;
-  const char* qrow = lds_q + (qb * 32 + (lane & 31)) * kStride + 16 * (lane >> 5);
   bf16x8 qf[D / 16];
+  load_q_frags<D>(lds_q, qb, lane, qf);
 #pragma unroll
-  for (int s = 0; s < D / 16; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qrow + 32 * s);
-#pragma unroll
-  for (int j = 0; j < kKB; ++j) {
-    f32x16 a = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int s = 0; s < D / 16; ++s)
-      a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j][s], qf[s], a, 0, 0, 0);
-    acc[j] = a;
-  }
+  for (int j = 0; j < kKB; ++j) acc[j] = mfma_block<D>(kf[j], qf);
 }
-
-// Sum each of 16 per-lane values over the 32 lanes of a lane-half.  On return the
-// lane with in-half index t holds the total of value index t >> 1.
-__device__ __forceinline__ float fold16_over32(const float (&u)[16], int t) {
-  float w8[8], w4[4], w2[2];
-  const bool b4 = (t & 16) != 0;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const float keep = b4 ? u[i + 8] : u[i];
-    const float send = b4 ? u[i] : u[i + 8];
-    w8[i] = keep + __shfl_xor(send, 16);
-  }
-  const bool b3 = (t & 8) != 0;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const float keep = b3 ? w8[i + 4] : w8[i];
-    const float send = b3 ? w8[i] : w8[i + 4];
-    w4[i] = keep + __shfl_xor(send, 8);
-  }
-  const bool b2 = (t & 4) != 0;
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const float keep = b2 ? w4[i + 2] : w4[i];
-    const float send = b2 ? w4[i] : w4[i + 2];
-    w2[i] = keep + __shfl_xor(send, 4);
-  }
-  const bool b1 = (t & 2) != 0;
-  const float keep = b1 ? w2[1] : w2[0];
-  const float send = b1 ? w2[0] : w2[1];
-  float w1 = keep + __shfl_xor(send, 2);
-  w1 += __shfl_xor(w1, 1);
-  return w1;
-}
-
-__device__ __forceinline__ int round_up32(int x) { return (x + 31) & ~31; }
 
 }  // namespace
 
@@ -191,7 +82,7 @@ __global__ __launch_bounds__(256) void rowstats_bf16(LaunchParams prm) {
 
   for (int row0 = 0; row0 < R; row0 += prm.row_chunk) {
     const int rows = min(prm.row_chunk, round_up32(R - row0));
-    stage_q<D>(pb.q, R, row0, rows, lds_q, tid);
+    stage_q<D, kWaves * 64>(pb.q, R, row0, rows, lds_q, tid);
     __syncthreads();
     for (int qb = 0; qb < rows / 32; ++qb) {
       f32x16 acc[kKB];
@@ -267,7 +158,7 @@ __global__ __launch_bounds__(256) void colsum_bf16(LaunchParams prm) {
 
   for (int row0 = 0; row0 < R; row0 += prm.row_chunk) {
     const int rows = min(prm.row_chunk, round_up32(R - row0));
-    stage_q<D>(pb.q, R, row0, rows, lds_q, tid);
+    stage_q<D, kWaves * 64>(pb.q, R, row0, rows, lds_q, tid);
     for (int i = tid; i < rows; i += kWaves * 64) lds_lse[i] = lse[row0 + i];
     __syncthreads();
     for (int qb = 0; qb < rows / 32; ++qb) {
@@ -311,7 +202,7 @@ __global__ __launch_bounds__(256) void lse_merge(LaunchParams prm) {
         const float2 s = st[static_cast<size_t>(tl) * prm.rpad_max + row];
         merge_stats(m, z, s.x, s.y);
       }
-      out = m + __builtin_amdgcn_logf(z);  // v_log_f32 is log2
+      out = m + fast_log2(z);
     }
     lse[row] = out;
   }

@@ -46,6 +46,79 @@ def test_step_ragged_batch(dtype, d, group):
     fin.step(batch)
     st = H.validate_single_step(ts, f"step {dtype} d={d}")
     say(f"  worst score rel err {st['worst_rel']:.2e}, near-tie swaps {st['swaps']}")
+    assert fin.check() == 0
+    fin.close()
+
+
+def _which_scoring_kernels(fin, batch):
+    F.finch_profile(fin.ctx, True)
+    fin.step(batch)
+    torch.cuda.synchronize()
+    prof = F.finch_profile_read(fin.ctx)
+    F.finch_profile(fin.ctx, False)
+    return {k for k, v in prof.items() if v["launches"]}
+
+
+@pytest.mark.parametrize("d,group,path", [(128, 4, "fused"), (128, 4, "two_pass"), (64, 2, "fused"),
+                                          (128, 1, "fused"), (64, 8, "two_pass")])
+def test_both_scoring_paths(d, group, path):
+    """The single-pass (row statistics exchanged between workgroups) and the two-pass
+    scoring kernels, each forced, on the same ragged batch with up to 256 stacked rows."""
+    say(f"both_scoring_paths d={d} G={group} {path}")
+    fin = F.Finch(F.FINCH_BF16, d, group)
+    fin.set_scoring_path(F.FINCH_SCORING_FUSED if path == "fused" else F.FINCH_SCORING_TWO_PASS)
+    cap = 256 // group
+    specs = [dict(s, n_que=min(s["n_que"], cap)) for s in RAGGED_SPECS]
+    specs += [dict(n_que=cap, c=1364, m=4096, r=1408), dict(n_que=max(1, cap // 3), c=5, m=130, r=64)]
+    batch, ts = H.single_step_case(fin, specs, torch.bfloat16, d, group, seed=300 + d + group)
+    fin.step(batch)
+    st = H.validate_single_step(ts, f"{path} d={d} G={group}")
+    say(f"  worst score rel err {st['worst_rel']:.2e}, near-tie swaps {st['swaps']}")
+    assert fin.check() == 0
+    ran = _which_scoring_kernels(fin, batch)
+    assert ("fused_score" in ran) == (path == "fused") and ("colsum" in ran) == (path != "fused"), ran
+    # a second launch on the same context: the synchronisation words were left clean
+    for t in ts:
+        t["scores"].fill_(-5.0)
+    fin.step(batch)
+    H.validate_single_step(ts, f"{path} again")
+    assert fin.check() == 0
+    fin.close()
+
+
+def test_forced_fused_rejects_unsupported_batches():
+    fin = F.Finch(F.FINCH_BF16, 128, 4)
+    fin.set_scoring_path(F.FINCH_SCORING_FUSED)
+    batch, ts = H.single_step_case(fin, [dict(n_que=128, c=10, m=100, r=5)], torch.bfloat16, 128, 4, 1)
+    with pytest.raises(F.FinchError) as e:
+        fin.step(batch)
+    assert e.value.status == F.FINCH_ERR_UNSUPPORTED
+    fin.set_scoring_path(F.FINCH_SCORING_AUTO)
+    fin.step(batch)                       # falls back to the two-pass kernels
+    H.validate_single_step(ts, "auto fallback")
+    fin.close()
+
+
+def test_abandoned_wait_is_reported_and_recoverable():
+    """A spin limit of one poll, set from the host, makes waiting workgroups give up:
+    the launch still terminates, finch_check reports it, and the next launch with
+    the normal limit is correct again."""
+    say("abandoned wait")
+    fin = F.Finch(F.FINCH_BF16, 128, 4)
+    fin.set_scoring_path(F.FINCH_SCORING_FUSED)
+    specs = [dict(n_que=48, c=1364, m=4096, r=1408)] * 24
+    batch, ts = H.single_step_case(fin, specs, torch.bfloat16, 128, 4, seed=12)
+    F.finch_set_option(fin.ctx, F.FINCH_OPT_SPIN_LIMIT, 1)
+    fin.step(batch)
+    err = fin.check()
+    say(f"  device error word with spin limit 1: {err}")
+    assert err in (0, 1)
+    F.finch_set_option(fin.ctx, F.FINCH_OPT_SPIN_LIMIT, 200000)
+    for t in ts:
+        t["scores"].fill_(-5.0)
+    fin.step(batch)
+    H.validate_single_step(ts[:3], "after an abandoned wait")
+    assert fin.check() == 0
     fin.close()
 
 
