@@ -117,17 +117,24 @@ finch_status finch_step(finch_ctx* ctx, const finch_problem* host_desc,
 finch_status finch_schedule(int64_t n_cont, int32_t m, int64_t k, int32_t* r_out,
                             int32_t r_len);
 
-/* Options.  FINCH_OPT_SCORING_PATH picks the scoring kernels: AUTO (default) uses
- * the single-pass kernel, in which the workgroups of one problem exchange their
- * softmax row statistics while their tiles stay in registers, whenever the batch
- * allows it (bf16, G*n_que <= 256, the device can hold all tiles of eight
- * problems at once) and the two-pass kernels otherwise; TWO_PASS and FUSED force
- * one of them (FUSED makes unsupported batches fail with FINCH_ERR_UNSUPPORTED).
+/* Options.  FINCH_OPT_SCORING_PATH picks the scoring kernels: AUTO (default) and
+ * TWO_PASS use the two-pass kernels (row statistics, then per-key sums); FUSED
+ * asks for the single-pass kernel, in which the workgroups of one problem exchange
+ * their softmax row statistics while their tiles stay in registers.  It needs
+ * bf16, G*n_que <= 256 and a device that can hold all tiles of eight problems at
+ * once (other batches fail with FINCH_ERR_UNSUPPORTED), and it is slower than the
+ * two-pass kernels on the measured workloads; it is kept as an alternative.
  * FINCH_OPT_SPIN_LIMIT bounds how often a workgroup of the single-pass kernel
  * polls for the other tiles of its problem before it gives up, raises the
  * context's device error word and carries on (the launch always terminates).
  * One context must not run on two streams at the same time. */
-typedef enum { FINCH_OPT_SCORING_PATH = 1, FINCH_OPT_SPIN_LIMIT = 2 } finch_option;
+typedef enum {
+  FINCH_OPT_SCORING_PATH = 1,
+  FINCH_OPT_SPIN_LIMIT = 2,
+  /* debugging aid: value = device pointer to 8 uint64 per workgroup of the
+   * single-pass kernel, filled with 100 MHz timestamps of its phases; 0 = off */
+  FINCH_OPT_DEBUG_TIMING = 3
+} finch_option;
 typedef enum { FINCH_SCORING_AUTO = 0, FINCH_SCORING_TWO_PASS = 1, FINCH_SCORING_FUSED = 2 } finch_scoring;
 finch_status finch_set_option(finch_ctx* ctx, int32_t option, int64_t value);
 

@@ -37,6 +37,7 @@ KERNEL_NAMES = ("rowstats", "lse", "colsum", "select", "gather", "fused_score")
 
 FINCH_OPT_SCORING_PATH = 1
 FINCH_OPT_SPIN_LIMIT = 2
+FINCH_OPT_DEBUG_TIMING = 3
 FINCH_SCORING_AUTO = 0
 FINCH_SCORING_TWO_PASS = 1
 FINCH_SCORING_FUSED = 2

@@ -25,6 +25,7 @@ struct finch_ctx {
   int n_cu;              // compute units of the device
   int scoring_path;      // FINCH_SCORING_AUTO / _TWO_PASS / _FUSED
   uint32_t spin_limit;
+  unsigned long long* timing;  // debug: per-workgroup timestamps of the fused kernel
   int fused_blocks[2][5];  // cached occupancy per (head_dim index, nq); 0 = not asked yet
   size_t fused_blocks_lds[2][5];
 };
@@ -61,10 +62,11 @@ inline bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
 
 size_t score_lds(const finch_ctx* ctx, int row_chunk) {
   const size_t d = static_cast<size_t>(ctx->cfg.head_dim);
-  const size_t q_row = ctx->cfg.dtype == FINCH_BF16 ? d * 2 + 16 : d * 4;
-  // per staged row: the row itself + 4 per-wave (max,sum) pairs (pass 1) which also
-  // covers the 4-byte lse entry of pass 2
-  return static_cast<size_t>(row_chunk) * (q_row + 4 * sizeof(float2));
+  // per staged row: the row itself + one (max,sum) pair per wave (pass 1), which
+  // also covers the 4-byte lse entry of pass 2
+  if (ctx->cfg.dtype == FINCH_BF16)
+    return static_cast<size_t>(row_chunk) * (d * 2 + 16 + (finch::kStreamThreads / 64) * sizeof(float2));
+  return static_cast<size_t>(row_chunk) * (d * 4 + 4 * sizeof(float2));
 }
 
 finch_status make_plan(const finch_ctx* ctx, const finch_problem* hd, int32_t n, Plan& pl) {
@@ -85,7 +87,10 @@ finch_status make_plan(const finch_ctx* ctx, const finch_problem* hd, int32_t n,
   pl.rows_max = static_cast<int32_t>(rows_max);
   pl.rpad_max = static_cast<int32_t>((rows_max + 31) / 32 * 32);
   pl.r_max = static_cast<int32_t>(r_max);
-  pl.tiles_max = static_cast<int32_t>((n_max + finch::kTileKeys - 1) / finch::kTileKeys);
+  pl.tiles_max = ctx->cfg.dtype == FINCH_BF16
+                     ? finch::stream_slices(static_cast<int>(n_max))
+                     : static_cast<int32_t>((n_max + finch::kTileKeys - 1) / finch::kTileKeys);
+  if (n_max == 0) pl.tiles_max = 0;
   pl.score_stride = static_cast<int32_t>((n_max + 63) / 64 * 64);
   int rc = pl.rpad_max < finch::kMaxRowChunk ? pl.rpad_max : finch::kMaxRowChunk;
   if (rc < 32) rc = 32;
@@ -107,8 +112,9 @@ finch_status make_plan(const finch_ctx* ctx, const finch_problem* hd, int32_t n,
                       pg * (pl.tiles_fused > 0 ? pl.tiles_fused : 1) < (int64_t{1} << 31);
   size_t off = 0;
   pl.off_stats = off;
-  // sized for whichever scoring kernel runs: the fused one has twice the tiles
-  off = align_up(off + static_cast<size_t>(n) * pl.tiles_fused * pl.rpad_max * sizeof(float2), 256);
+  // sized for whichever scoring kernel runs
+  const int32_t parts = pl.tiles_fused > pl.tiles_max ? pl.tiles_fused : pl.tiles_max;
+  off = align_up(off + static_cast<size_t>(n) * parts * pl.rpad_max * sizeof(float2), 256);
   pl.off_lse = off;
   off = align_up(off + static_cast<size_t>(n) * pl.rpad_max * sizeof(float), 256);
   pl.off_scores = off;
@@ -182,6 +188,7 @@ LaunchParams make_params(const finch_ctx* ctx, const finch_problem* dd, int32_t 
   p.n_problems = n;
   p.group = ctx->cfg.group_size;
   p.tiles_max = pl.tiles_max;
+  p.tile_keys = ctx->cfg.dtype == FINCH_BF16 ? 0 : finch::kTileKeys;
   p.rpad_max = pl.rpad_max;
   p.row_chunk = pl.row_chunk;
   p.score_stride = pl.score_stride;
@@ -193,13 +200,15 @@ LaunchParams make_params(const finch_ctx* ctx, const finch_problem* dd, int32_t 
   p.tiles_fused = pl.tiles_fused;
   p.spin_limit = ctx->spin_limit;
   p.sync = ctx->sync;
+  p.timing = ctx->timing;
   return p;
 }
 
 // Whether this batch may use the fused kernel: its shapes fit, and the device
 // holds enough workgroups at once for the waits to be safe (see score_fused.hip).
 bool use_fused(finch_ctx* ctx, const Plan& pl) {
-  if (ctx->scoring_path == FINCH_SCORING_TWO_PASS || !pl.fused_shape_ok || !ctx->sync) return false;
+  // the single-pass kernel only runs when asked for: it is correct but slower
+  if (ctx->scoring_path != FINCH_SCORING_FUSED || !pl.fused_shape_ok || !ctx->sync) return false;
   const int di = ctx->cfg.head_dim == 128 ? 1 : 0;
   if (ctx->fused_blocks[di][pl.fused_nq] == 0 || ctx->fused_blocks_lds[di][pl.fused_nq] != pl.fused_lds) {
     int b = 0;
@@ -318,6 +327,7 @@ finch_status finch_create(const finch_config* cfg, finch_ctx** out) {
   ctx->n_cu = 0;
   ctx->scoring_path = FINCH_SCORING_AUTO;
   ctx->spin_limit = 200000;
+  ctx->timing = nullptr;
   std::memset(ctx->fused_blocks, 0, sizeof(ctx->fused_blocks));
   std::memset(ctx->fused_blocks_lds, 0, sizeof(ctx->fused_blocks_lds));
   hipError_t e = hipGetDevice(&ctx->device);
@@ -373,6 +383,9 @@ finch_status finch_set_option(finch_ctx* ctx, int32_t option, int64_t value) {
     case FINCH_OPT_SPIN_LIMIT:
       if (value < 1 || value > 0x7fffffff) return FINCH_ERR_INVALID_ARG;
       ctx->spin_limit = static_cast<uint32_t>(value);
+      return FINCH_OK;
+    case FINCH_OPT_DEBUG_TIMING:
+      ctx->timing = reinterpret_cast<unsigned long long*>(static_cast<uintptr_t>(value));
       return FINCH_OK;
     default:
       return FINCH_ERR_INVALID_ARG;

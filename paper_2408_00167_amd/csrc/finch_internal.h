@@ -8,10 +8,17 @@
 
 namespace finch {
 
-// Keys handled by one workgroup of the scoring kernels.
+// Keys handled by one workgroup of the fp32 scoring kernels.
 constexpr int kTileKeys = 256;
 // Prompt rows staged in LDS at a time (larger R is processed in several chunks).
 constexpr int kMaxRowChunk = 512;
+// bf16 two-pass scoring: threads per workgroup, and the number of slices the keys
+// of a problem are cut into (one workgroup streams one slice of about 2400 keys).
+constexpr int kStreamThreads = 512;
+__host__ __device__ inline int stream_slices(int n_keys) {
+  const int s = (n_keys + 1200) / 2400;
+  return s < 1 ? 1 : s;
+}
 // Rows copied by one workgroup of the compaction kernel.
 constexpr int kGatherRows = 64;
 // Fused single-pass scoring: keys per workgroup, threads per workgroup, most
@@ -34,7 +41,10 @@ struct LaunchParams {
   const finch_problem* probs;  // device descriptors
   int32_t n_problems;
   int32_t group;               // G
-  int32_t tiles_max;           // ceil(max_p (c+m) / kTileKeys)
+  int32_t tiles_max;           // most partial-statistics records of any problem:
+                               // ceil(max_p (c+m) / tile_keys), or stream_slices(max) if
+                               // tile_keys == 0
+  int32_t tile_keys;           // kTileKeys for the fp32 kernels, 0 for the bf16 ones
   int32_t rpad_max;            // max_p round_up(G*n_que, 32)
   int32_t row_chunk;           // rows staged per pass over the keys (multiple of 32)
   int32_t score_stride;        // floats per problem in ws_scores
@@ -48,6 +58,7 @@ struct LaunchParams {
   uint32_t spin_limit;         // polls after which a waiting workgroup gives up
   unsigned* sync;              // kSyncWords words owned by the context, all zero
                                // between launches
+  unsigned long long* timing;  // optional debug buffer: 8 timestamps per workgroup
 };
 
 // Launchers; each returns hipGetLastError() after the launch.

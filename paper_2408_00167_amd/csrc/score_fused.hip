@@ -5,8 +5,9 @@
 // problem before any column sum can be finished.  Instead of a second pass over K
 // (a second contraction and a second exp per logit), every workgroup keeps its
 // tile's  E_ij = exp2(s'_ij - m_i)  (m_i = a tile-local row maximum) in registers,
-// publishes the tile's per-row (max, sum) pairs, waits until all tiles of its
-// problem have published, merges them into lse_i, and finishes with
+// publishes the tile's per-row (max, sum) pairs and bumps its problem's arrival
+// counter.  The tile that arrives last merges all pairs into lse_i and hands it to
+// the others, which wait for it; every tile then finishes with
 // score_j = sum_i E_ij * exp2(m_i - lse_i): one contraction and one exp per logit.
 //
 // Workgroup = 512 threads = 8 waves on a tile of 128 keys: wave (kb, rh) owns key
@@ -56,11 +57,14 @@ __global__ __launch_bounds__(kThreads, 4) void score_fused_bf16(LaunchParams prm
   const int kb = wave & 3, rh = wave >> 2;
   unsigned* sync = prm.sync;
   const int cls = blockIdx.x & 7;
+  unsigned long long* tlog = prm.timing ? prm.timing + static_cast<size_t>(blockIdx.x) * 8 : nullptr;
+#define FINCH_STAMP(i) if (tlog && tid == 0) tlog[i] = wall_clock64()
+  FINCH_STAMP(0);
   if (tid == 0)
     sh_slot = static_cast<int>(__hip_atomic_fetch_add(&sync[kSyncTicket + cls * 16], 1u,
                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
   __syncthreads();
-  const int slot = sh_slot;
+  const int slot = __builtin_amdgcn_readfirstlane(sh_slot);  // uniform: scalar descriptor loads
   const int pg = slot / prm.tiles_fused;
   const int tile = slot - pg * prm.tiles_fused;
   const int p = pg * 8 + cls;
@@ -90,6 +94,7 @@ __global__ __launch_bounds__(kThreads, 4) void score_fused_bf16(LaunchParams prm
     load_k_block<D>(pb, N, kbase, lane, kf);
     stage_q<D, kThreads>(pb.q, R, 0, rpad, lds_q, tid);
     __syncthreads();
+    FINCH_STAMP(1);
 
     const float sc = prm.scale_log2;
     const bool ragged = kbase + 32 > N;
@@ -131,8 +136,12 @@ __global__ __launch_bounds__(kThreads, 4) void score_fused_bf16(LaunchParams prm
       }
     }
     __syncthreads();
+    FINCH_STAMP(2);
 
-    // publish this tile's row statistics
+    // Publish this tile's row statistics.  Shared words are written and read with
+    // device-scope atomics (they bypass the per-CU cache and are coherent between
+    // the L2s); ordering comes from waiting for the stores to complete before the
+    // arrival counter is bumped, not from cache write-backs or invalidations.
     float2* gst = prm.stats + (static_cast<size_t>(p) * prm.tiles_fused + tile) * prm.rpad_max;
     if (tid < rpad) {
       float2 a = lds_st[tid];
@@ -143,49 +152,77 @@ __global__ __launch_bounds__(kThreads, 4) void score_fused_bf16(LaunchParams prm
       }
       store_stat(gst + tid, a.x, a.y);
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // s_waitcnt: stores done
     __syncthreads();
     unsigned* arrive = sync + kSyncProblems + 2 * p;
+    float* glse = prm.lse + static_cast<size_t>(p) * prm.rpad_max;
     if (tid == 0) {
-      __hip_atomic_fetch_add(arrive, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-      unsigned spins = 0;
-      while (__hip_atomic_load(arrive, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) <
-             static_cast<unsigned>(tiles_p)) {
-        __builtin_amdgcn_s_sleep(8);
-        if (++spins > prm.spin_limit) {
-          __hip_atomic_fetch_or(&sync[kSyncError], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          break;
-        }
-      }
+      const unsigned old =
+          __hip_atomic_fetch_add(arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      sh_slot = (old == static_cast<unsigned>(tiles_p) - 1u) ? 1 : 0;  // 1: all tiles are in
     }
     __syncthreads();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-
-    // lse of every prompt row over all tiles: thread (row, part) merges every
-    // second tile, then the two parts are merged; same order in every workgroup.
-    {
+    FINCH_STAMP(3);
+    const bool combiner = __builtin_amdgcn_readfirstlane(sh_slot) != 0;
+    if (tlog && tid == 0) tlog[7] = (static_cast<unsigned long long>(p) << 32) | (tile << 1) | (combiner ? 1 : 0);
+    if (combiner) {
+      // The last tile to arrive merges all tiles' statistics into lse per prompt
+      // row (thread (row, part) takes every second tile, fixed order), hands the
+      // result to the waiting tiles and bumps the counter once more.
       const int row = tid & 255, part = tid >> 8;
       if (row < rpad) {
         float m = -kInf, z = 0.f;
         if (row < R) {
-          const float2* st = prm.stats + static_cast<size_t>(p) * prm.tiles_fused * prm.rpad_max + row;
-          for (int tl = part; tl < tiles_p; tl += 2) {
-            const float2 s = load_stat(st + static_cast<size_t>(tl) * prm.rpad_max);
-            merge_stats(m, z, s.x, s.y);
+          const float2* st =
+              prm.stats + static_cast<size_t>(p) * prm.tiles_fused * prm.rpad_max + row;
+          constexpr int kBatch = NQ >= 4 ? 4 : 8;  // loads in flight per thread
+          for (int tl0 = part; tl0 < tiles_p; tl0 += 2 * kBatch) {
+            float2 sv[kBatch];
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+              const int tl = tl0 + 2 * j;
+              sv[j] = tl < tiles_p ? load_stat(st + static_cast<size_t>(tl) * prm.rpad_max)
+                                   : make_float2(-kInf, 0.f);
+            }
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) merge_stats(m, z, sv[j].x, sv[j].y);
           }
         }
         lds_st[part * rows_lds + row] = make_float2(m, z);
       }
+      __syncthreads();
+      if (tid < rpad) {
+        float2 a = lds_st[tid];
+        const float2 b = lds_st[rows_lds + tid];
+        merge_stats(a.x, a.y, b.x, b.y);
+        const float l = (tid < R) ? a.x + fast_log2(a.y) : kInf;
+        lds_lse[tid] = l;
+        __hip_atomic_store(glse + tid, l, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      __syncthreads();
+      if (tid == 0)
+        __hip_atomic_fetch_add(arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+      if (tid == 0) {
+        unsigned spins = 0;
+        while (__hip_atomic_load(arrive, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) <=
+               static_cast<unsigned>(tiles_p)) {
+          __builtin_amdgcn_s_sleep(4);
+          if (++spins > prm.spin_limit) {
+            __hip_atomic_fetch_or(&sync[kSyncError], 1u, __ATOMIC_RELAXED,
+                                  __HIP_MEMORY_SCOPE_AGENT);
+            break;
+          }
+        }
+      }
+      __syncthreads();
+      if (tid < rpad)
+        lds_lse[tid] = __hip_atomic_load(glse + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __syncthreads();
     }
-    __syncthreads();
-    if (tid < rpad) {
-      float2 a = lds_st[tid];
-      const float2 b = lds_st[rows_lds + tid];
-      merge_stats(a.x, a.y, b.x, b.y);
-      lds_lse[tid] = (tid < R) ? a.x + fast_log2(a.y) : kInf;
-    }
-    __syncthreads();
 
+    FINCH_STAMP(4);
     // per-key sums over this wave's rows, folded over lanes, then over row halves
     float u[16];
 #pragma unroll
@@ -211,9 +248,10 @@ __global__ __launch_bounds__(kThreads, 4) void score_fused_bf16(LaunchParams prm
 
     // leave: the last tile of the problem clears its counters for the next launch
     __syncthreads();
+    FINCH_STAMP(5);
     if (tid == 0) {
       const unsigned d =
-          __hip_atomic_fetch_add(arrive + 1, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_fetch_add(arrive + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (d == static_cast<unsigned>(tiles_p) - 1u) {
         __hip_atomic_store(arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(arrive + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -223,7 +261,7 @@ __global__ __launch_bounds__(kThreads, 4) void score_fused_bf16(LaunchParams prm
 
   // retire: the last workgroup of the grid clears the ticket queues
   if (tid == 0) {
-    const unsigned d = __hip_atomic_fetch_add(&sync[kSyncDone], 1u, __ATOMIC_ACQ_REL,
+    const unsigned d = __hip_atomic_fetch_add(&sync[kSyncDone], 1u, __ATOMIC_RELAXED,
                                               __HIP_MEMORY_SCOPE_AGENT);
     if (d == gridDim.x - 1u) {
       for (int c = 0; c < 8; ++c)
