@@ -117,29 +117,30 @@ finch_status finch_step(finch_ctx* ctx, const finch_problem* host_desc,
 finch_status finch_schedule(int64_t n_cont, int32_t m, int64_t k, int32_t* r_out,
                             int32_t r_len);
 
-/* Options.  FINCH_OPT_SCORING_PATH picks the scoring kernels: AUTO (default) and
- * TWO_PASS use the two-pass kernels (row statistics, then per-key sums); FUSED
- * asks for the single-pass kernel, in which the workgroups of one problem exchange
- * their softmax row statistics while their tiles stay in registers.  It needs
- * bf16, G*n_que <= 256 and a device that can hold all tiles of eight problems at
- * once (other batches fail with FINCH_ERR_UNSUPPORTED), and it is slower than the
- * two-pass kernels on the measured workloads; it is kept as an alternative.
- * FINCH_OPT_SPIN_LIMIT bounds how often a workgroup of the single-pass kernel
- * polls for the other tiles of its problem before it gives up, raises the
- * context's device error word and carries on (the launch always terminates).
+/* Options.  FINCH_OPT_STEP_PATH picks how the stages are launched.  SEPARATE, and
+ * AUTO (default, = SEPARATE: it is the faster one on the measured workloads), use
+ * one kernel per stage: row statistics, merge, per-key sums, top-r, compaction.
+ * FUSED runs finch_step (and finch_score) as ONE kernel when the batch allows it
+ * (bf16, G*n_que <= 448; other batches fail with FINCH_ERR_UNSUPPORTED): its
+ * workgroups take pass-1, pass-2, top-r and copy work items from a queue and hand
+ * results to each other through device memory, so there are no kernel boundaries
+ * between the stages.
+ * FINCH_OPT_SPIN_LIMIT bounds how often a work item of the FUSED kernel polls for
+ * results of work items that were started before it, before it gives up, raises
+ * the context's device error word and carries on, so a launch always terminates.
  * One context must not run on two streams at the same time. */
 typedef enum {
-  FINCH_OPT_SCORING_PATH = 1,
+  FINCH_OPT_STEP_PATH = 1,
   FINCH_OPT_SPIN_LIMIT = 2,
-  /* debugging aid: value = device pointer to 8 uint64 per workgroup of the
-   * single-pass kernel, filled with 100 MHz timestamps of its phases; 0 = off */
-  FINCH_OPT_DEBUG_TIMING = 3
+  /* tuning: target number of keys one workgroup of the bf16 scoring kernels
+   * streams (default 2400); a problem is cut into round((c+m)/value) slices */
+  FINCH_OPT_SLICE_KEYS = 3
 } finch_option;
-typedef enum { FINCH_SCORING_AUTO = 0, FINCH_SCORING_TWO_PASS = 1, FINCH_SCORING_FUSED = 2 } finch_scoring;
+typedef enum { FINCH_PATH_AUTO = 0, FINCH_PATH_SEPARATE = 1, FINCH_PATH_FUSED = 2 } finch_path;
 finch_status finch_set_option(finch_ctx* ctx, int32_t option, int64_t value);
 
 /* Synchronises `stream`, then reports the context's device error word in
- * *device_error (0 = none; bit 0 = a bounded wait was abandoned and the scores of
+ * *device_error (0 = none; bit 0 = a bounded wait was abandoned and the outputs of
  * that launch are invalid) and clears it.  The only call that blocks. */
 finch_status finch_check(finch_ctx* ctx, void* stream, int32_t* device_error);
 
@@ -157,7 +158,7 @@ typedef enum {
   FINCH_KERNEL_COLSUM = 2,   /* scoring pass 2: per-key sums of the weights  */
   FINCH_KERNEL_SELECT = 3,   /* top-r                                        */
   FINCH_KERNEL_GATHER = 4,   /* compaction                                   */
-  FINCH_KERNEL_FUSED_SCORE = 5, /* single-pass scoring (replaces 0..2)       */
+  FINCH_KERNEL_STEP = 5,     /* all stages in one kernel (replaces 0..4)     */
   FINCH_KERNEL_COUNT = 6
 } finch_kernel;
 finch_status finch_profile(finch_ctx* ctx, int32_t enable);

@@ -33,14 +33,14 @@ EXPORTED_SYMBOLS = (
     "finch_set_option", "finch_check",
 )
 
-KERNEL_NAMES = ("rowstats", "lse", "colsum", "select", "gather", "fused_score")
+KERNEL_NAMES = ("rowstats", "lse", "colsum", "select", "gather", "step")
 
-FINCH_OPT_SCORING_PATH = 1
+FINCH_OPT_STEP_PATH = 1
 FINCH_OPT_SPIN_LIMIT = 2
-FINCH_OPT_DEBUG_TIMING = 3
-FINCH_SCORING_AUTO = 0
-FINCH_SCORING_TWO_PASS = 1
-FINCH_SCORING_FUSED = 2
+FINCH_OPT_SLICE_KEYS = 3
+FINCH_PATH_AUTO = 0
+FINCH_PATH_SEPARATE = 1
+FINCH_PATH_FUSED = 2
 
 
 class FinchError(RuntimeError):
@@ -254,8 +254,8 @@ class Finch:
         except Exception:
             pass
 
-    def set_scoring_path(self, path: int) -> None:
-        finch_set_option(self.ctx, FINCH_OPT_SCORING_PATH, path)
+    def set_step_path(self, path: int) -> None:
+        finch_set_option(self.ctx, FINCH_OPT_STEP_PATH, path)
 
     def check(self, stream=None) -> int:
         import torch

@@ -20,14 +20,12 @@ struct finch_ctx {
   int prof_used;
   hipEvent_t* prof_ev;   // 2 * kProfPairs events, or nullptr
   int* prof_kind;        // kernel class of each pair
-  // fused scoring
+  // one-kernel-per-step path
   unsigned* sync;        // device, finch::kSyncWords words, zero between launches
   int n_cu;              // compute units of the device
-  int scoring_path;      // FINCH_SCORING_AUTO / _TWO_PASS / _FUSED
+  int step_path;         // FINCH_PATH_AUTO / _SEPARATE / _FUSED
   uint32_t spin_limit;
-  unsigned long long* timing;  // debug: per-workgroup timestamps of the fused kernel
-  int fused_blocks[2][5];  // cached occupancy per (head_dim index, nq); 0 = not asked yet
-  size_t fused_blocks_lds[2][5];
+  int slice_keys;        // target keys per workgroup slice of the bf16 scoring kernels
 };
 
 namespace {
@@ -44,9 +42,7 @@ enum Need : unsigned {
 struct Plan {
   int32_t n_max = 0, rows_max = 0, rpad_max = 0, r_max = 0, tiles_max = 0, row_chunk = 32;
   int32_t score_stride = 0;
-  int32_t tiles_fused = 0, fused_nq = 0;
-  bool fused_shape_ok = false;   // shapes allow the fused kernel (occupancy checked at launch)
-  size_t fused_lds = 0;
+  bool step_ok = false;   // the batch can run as one kernel per step
   size_t lds_bytes = 0;
   size_t off_stats = 0, off_lse = 0, off_scores = 0, total = 0;
 };
@@ -88,7 +84,7 @@ finch_status make_plan(const finch_ctx* ctx, const finch_problem* hd, int32_t n,
   pl.rpad_max = static_cast<int32_t>((rows_max + 31) / 32 * 32);
   pl.r_max = static_cast<int32_t>(r_max);
   pl.tiles_max = ctx->cfg.dtype == FINCH_BF16
-                     ? finch::stream_slices(static_cast<int>(n_max))
+                     ? finch::stream_slices(static_cast<int>(n_max), ctx->slice_keys)
                      : static_cast<int32_t>((n_max + finch::kTileKeys - 1) / finch::kTileKeys);
   if (n_max == 0) pl.tiles_max = 0;
   pl.score_stride = static_cast<int32_t>((n_max + 63) / 64 * 64);
@@ -103,18 +99,14 @@ finch_status make_plan(const finch_ctx* ctx, const finch_problem* hd, int32_t n,
   if (pg * (pl.tiles_max > 0 ? pl.tiles_max : 1) >= (int64_t{1} << 31)) return FINCH_ERR_CAPACITY;
   const int64_t gb = (static_cast<int64_t>(pl.r_max) + finch::kGatherRows - 1) / finch::kGatherRows;
   if (gb * n >= (int64_t{1} << 31)) return FINCH_ERR_CAPACITY;
-  pl.tiles_fused = static_cast<int32_t>((n_max + finch::kFusedKeys - 1) / finch::kFusedKeys);
-  pl.fused_nq = (pl.rpad_max + 63) / 64;
-  pl.fused_lds = finch::fused_lds_bytes(ctx->cfg.head_dim, pl.rpad_max);
-  pl.fused_shape_ok = ctx->cfg.dtype == FINCH_BF16 && pl.rpad_max >= 32 &&
-                      pl.rpad_max <= finch::kFusedMaxRows && n <= finch::kSyncMaxProblems &&
-                      pl.fused_lds + finch::kFusedStaticLds <= ctx->max_lds &&
-                      pg * (pl.tiles_fused > 0 ? pl.tiles_fused : 1) < (int64_t{1} << 31);
+  pl.step_ok = ctx->cfg.dtype == FINCH_BF16 && ctx->sync && n_max > 0 &&
+               pl.rpad_max <= finch::kStepMaxRows && pl.row_chunk == pl.rpad_max &&
+               pl.lds_bytes + finch::kStepStaticLds <= ctx->max_lds &&
+               n <= finch::kSyncMaxProblems &&
+               (2 * static_cast<int64_t>(pl.tiles_max) + 16) * n < (int64_t{1} << 31);
   size_t off = 0;
   pl.off_stats = off;
-  // sized for whichever scoring kernel runs
-  const int32_t parts = pl.tiles_fused > pl.tiles_max ? pl.tiles_fused : pl.tiles_max;
-  off = align_up(off + static_cast<size_t>(n) * parts * pl.rpad_max * sizeof(float2), 256);
+  off = align_up(off + static_cast<size_t>(n) * pl.tiles_max * pl.rpad_max * sizeof(float2), 256);
   pl.off_lse = off;
   off = align_up(off + static_cast<size_t>(n) * pl.rpad_max * sizeof(float), 256);
   pl.off_scores = off;
@@ -189,6 +181,7 @@ LaunchParams make_params(const finch_ctx* ctx, const finch_problem* dd, int32_t 
   p.group = ctx->cfg.group_size;
   p.tiles_max = pl.tiles_max;
   p.tile_keys = ctx->cfg.dtype == FINCH_BF16 ? 0 : finch::kTileKeys;
+  p.slice_keys = ctx->slice_keys;
   p.rpad_max = pl.rpad_max;
   p.row_chunk = pl.row_chunk;
   p.score_stride = pl.score_stride;
@@ -197,32 +190,10 @@ LaunchParams make_params(const finch_ctx* ctx, const finch_problem* dd, int32_t 
   p.stats = reinterpret_cast<float2*>(base + pl.off_stats);
   p.lse = reinterpret_cast<float*>(base + pl.off_lse);
   p.ws_scores = reinterpret_cast<float*>(base + pl.off_scores);
-  p.tiles_fused = pl.tiles_fused;
+  p.lds_bytes = static_cast<uint32_t>(pl.lds_bytes);
   p.spin_limit = ctx->spin_limit;
   p.sync = ctx->sync;
-  p.timing = ctx->timing;
   return p;
-}
-
-// Whether this batch may use the fused kernel: its shapes fit, and the device
-// holds enough workgroups at once for the waits to be safe (see score_fused.hip).
-bool use_fused(finch_ctx* ctx, const Plan& pl) {
-  // the single-pass kernel only runs when asked for: it is correct but slower
-  if (ctx->scoring_path != FINCH_SCORING_FUSED || !pl.fused_shape_ok || !ctx->sync) return false;
-  const int di = ctx->cfg.head_dim == 128 ? 1 : 0;
-  if (ctx->fused_blocks[di][pl.fused_nq] == 0 || ctx->fused_blocks_lds[di][pl.fused_nq] != pl.fused_lds) {
-    int b = 0;
-    if (finch::fused_blocks_per_cu(ctx->cfg.head_dim, pl.fused_nq, pl.fused_lds, &b) != hipSuccess) {
-      (void)hipGetLastError();
-      b = -1;
-    }
-    ctx->fused_blocks[di][pl.fused_nq] = b > 0 ? b : -1;
-    ctx->fused_blocks_lds[di][pl.fused_nq] = pl.fused_lds;
-  }
-  const int blocks = ctx->fused_blocks[di][pl.fused_nq];
-  if (blocks <= 0) return false;
-  const int64_t resident = static_cast<int64_t>(blocks) * ctx->n_cu;
-  return 8 * static_cast<int64_t>(pl.tiles_fused) <= resident;
 }
 
 finch_status hip_fail(finch_ctx* ctx, hipError_t e) {
@@ -255,14 +226,15 @@ finch_status run_score(finch_ctx* ctx, const LaunchParams& p, const Plan& pl, hi
   hipError_t e = hipSuccess;
   const int d = ctx->cfg.head_dim;
   const bool bf16 = ctx->cfg.dtype == FINCH_BF16;
-  if (use_fused(ctx, pl)) {
+  // AUTO = one kernel per stage: measured faster than the single kernel on MI355X
+  if (ctx->step_path == FINCH_PATH_FUSED && pl.step_ok) {
     {
-      ProfScope ps(ctx, FINCH_KERNEL_FUSED_SCORE, s);
-      e = finch::launch_fused_bf16(d, pl.fused_nq, p, pl.fused_lds, s);
+      ProfScope ps(ctx, FINCH_KERNEL_STEP, s);
+      e = finch::launch_step_bf16(d, p, pl.lds_bytes, /*parts=*/0, s);
     }
     return e == hipSuccess ? FINCH_OK : hip_fail(ctx, e);
   }
-  if (ctx->scoring_path == FINCH_SCORING_FUSED) return FINCH_ERR_UNSUPPORTED;
+  if (ctx->step_path == FINCH_PATH_FUSED) return FINCH_ERR_UNSUPPORTED;
   {
     ProfScope ps(ctx, FINCH_KERNEL_ROWSTATS, s);
     e = bf16 ? finch::launch_rowstats_bf16(d, p, pl.lds_bytes, s)
@@ -325,11 +297,9 @@ finch_status finch_create(const finch_config* cfg, finch_ctx** out) {
   ctx->prof_kind = nullptr;
   ctx->sync = nullptr;
   ctx->n_cu = 0;
-  ctx->scoring_path = FINCH_SCORING_AUTO;
+  ctx->step_path = FINCH_PATH_AUTO;
   ctx->spin_limit = 200000;
-  ctx->timing = nullptr;
-  std::memset(ctx->fused_blocks, 0, sizeof(ctx->fused_blocks));
-  std::memset(ctx->fused_blocks_lds, 0, sizeof(ctx->fused_blocks_lds));
+  ctx->slice_keys = finch::kDefaultSliceKeys;
   hipError_t e = hipGetDevice(&ctx->device);
   if (e == hipSuccess) {
     int v = 0;
@@ -344,8 +314,8 @@ finch_status finch_create(const finch_config* cfg, finch_ctx** out) {
                                  : finch::set_max_lds_f32(ctx->max_lds);
   }
   if (e == hipSuccess && cfg->dtype == FINCH_BF16) {
-    // the fused kernel also has a few bytes of static LDS
-    e = finch::set_max_lds_fused(ctx->max_lds - finch::kFusedStaticLds);
+    // the one-kernel-per-step path also has a few bytes of static LDS
+    e = finch::set_max_lds_step(ctx->max_lds - finch::kStepStaticLds);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->sync), finch::kSyncWords * sizeof(unsigned));
     if (e == hipSuccess) e = hipMemset(ctx->sync, 0, finch::kSyncWords * sizeof(unsigned));
   }
@@ -374,18 +344,18 @@ finch_status finch_destroy(finch_ctx* ctx) {
 finch_status finch_set_option(finch_ctx* ctx, int32_t option, int64_t value) {
   if (!ctx) return FINCH_ERR_INVALID_ARG;
   switch (option) {
-    case FINCH_OPT_SCORING_PATH:
-      if (value != FINCH_SCORING_AUTO && value != FINCH_SCORING_TWO_PASS &&
-          value != FINCH_SCORING_FUSED)
+    case FINCH_OPT_STEP_PATH:
+      if (value != FINCH_PATH_AUTO && value != FINCH_PATH_SEPARATE && value != FINCH_PATH_FUSED)
         return FINCH_ERR_INVALID_ARG;
-      ctx->scoring_path = static_cast<int>(value);
+      ctx->step_path = static_cast<int>(value);
       return FINCH_OK;
     case FINCH_OPT_SPIN_LIMIT:
       if (value < 1 || value > 0x7fffffff) return FINCH_ERR_INVALID_ARG;
       ctx->spin_limit = static_cast<uint32_t>(value);
       return FINCH_OK;
-    case FINCH_OPT_DEBUG_TIMING:
-      ctx->timing = reinterpret_cast<unsigned long long*>(static_cast<uintptr_t>(value));
+    case FINCH_OPT_SLICE_KEYS:
+      if (value < 256 || value > (1 << 24)) return FINCH_ERR_INVALID_ARG;
+      ctx->slice_keys = static_cast<int>(value);
       return FINCH_OK;
     default:
       return FINCH_ERR_INVALID_ARG;
@@ -518,6 +488,19 @@ finch_status finch_step(finch_ctx* ctx, const finch_problem* host_desc,
   if (n == 0) return FINCH_OK;
   const LaunchParams p = make_params(ctx, dev_desc, n, pl, ws);
   hipStream_t s = static_cast<hipStream_t>(stream);
+  // AUTO = one kernel per stage: measured faster than the single kernel on MI355X
+  if (ctx->step_path == FINCH_PATH_FUSED && pl.step_ok) {
+    hipError_t e;
+    {
+      ProfScope ps(ctx, FINCH_KERNEL_STEP, s);
+      // copy items per problem: about 512 kept rows each
+      int parts = (pl.r_max + 511) / 512;
+      parts = parts < 1 ? 1 : parts > 16 ? 16 : parts;
+      e = finch::launch_step_bf16(ctx->cfg.head_dim, p, pl.lds_bytes, parts, s);
+    }
+    return e == hipSuccess ? FINCH_OK : hip_fail(ctx, e);
+  }
+  if (ctx->step_path == FINCH_PATH_FUSED && pl.tiles_max > 0) return FINCH_ERR_UNSUPPORTED;
   if ((st = run_score(ctx, p, pl, s)) != FINCH_OK) return st;
   if (pl.r_max == 0) return FINCH_OK;
   if ((st = run_select(ctx, p, s)) != FINCH_OK) return st;

@@ -15,23 +15,22 @@ constexpr int kMaxRowChunk = 512;
 // bf16 two-pass scoring: threads per workgroup, and the number of slices the keys
 // of a problem are cut into (one workgroup streams one slice of about 2400 keys).
 constexpr int kStreamThreads = 512;
-__host__ __device__ inline int stream_slices(int n_keys) {
-  const int s = (n_keys + 1200) / 2400;
+constexpr int kDefaultSliceKeys = 2400;
+__host__ __device__ inline int stream_slices(int n_keys, int slice_keys) {
+  const int s = (n_keys + slice_keys / 2) / slice_keys;
   return s < 1 ? 1 : s;
 }
 // Rows copied by one workgroup of the compaction kernel.
 constexpr int kGatherRows = 64;
-// Fused single-pass scoring: keys per workgroup, threads per workgroup, most
-// prompt rows (padded to 32) it can keep in registers, and the layout of the
-// context-owned synchronisation words (all uint32).
-constexpr int kFusedKeys = 128;
-constexpr int kFusedThreads = 512;
-constexpr int kFusedMaxRows = 256;
-constexpr int kFusedStaticLds = 256;  // upper bound of the fused kernel's static LDS
-constexpr int kSyncTicket = 0;      // 8 ticket counters, 16 words apart
+// One-kernel-per-step path: most prompt rows (padded to 32) it is compiled for, an
+// upper bound of its static LDS, and the layout of the context-owned
+// synchronisation words (all uint32, all zero between launches).
+constexpr int kStepMaxRows = 448;
+constexpr int kStepStaticLds = 256;
+constexpr int kSyncTicket = 0;      // next work item of the current launch
 constexpr int kSyncDone = 128;      // workgroups of the current launch that retired
 constexpr int kSyncError = 129;     // sticky error bits (bit 0: a wait ran past its limit)
-constexpr int kSyncProblems = 256;  // then per problem: {arrived, departed}
+constexpr int kSyncProblems = 256;  // then per problem: {pass-1 arrivals, pass-2 arrivals}
 constexpr int kSyncMaxProblems = 32768;
 constexpr int kSyncWords = kSyncProblems + 2 * kSyncMaxProblems;
 
@@ -45,6 +44,7 @@ struct LaunchParams {
                                // ceil(max_p (c+m) / tile_keys), or stream_slices(max) if
                                // tile_keys == 0
   int32_t tile_keys;           // kTileKeys for the fp32 kernels, 0 for the bf16 ones
+  int32_t slice_keys;          // target keys per slice of the bf16 kernels
   int32_t rpad_max;            // max_p round_up(G*n_que, 32)
   int32_t row_chunk;           // rows staged per pass over the keys (multiple of 32)
   int32_t score_stride;        // floats per problem in ws_scores
@@ -52,13 +52,11 @@ struct LaunchParams {
   float2* stats;               // [P][tiles_max][rpad_max] partial (max, sum) per tile
   float* lse;                  // [P][rpad_max] log2-domain log-sum-exp per prompt row
   float* ws_scores;            // [P][score_stride] used when desc.scores == NULL
-  // fused single-pass scoring only
-  int32_t tiles_fused;         // ceil(max_p (c+m) / kFusedKeys); stats is then
-                               // [P][tiles_fused][rpad_max]
+  // one-kernel-per-step path only
+  uint32_t lds_bytes;          // dynamic LDS of the launch
   uint32_t spin_limit;         // polls after which a waiting workgroup gives up
   unsigned* sync;              // kSyncWords words owned by the context, all zero
                                // between launches
-  unsigned long long* timing;  // optional debug buffer: 8 timestamps per workgroup
 };
 
 // Launchers; each returns hipGetLastError() after the launch.
@@ -70,11 +68,9 @@ hipError_t launch_colsum_f32(int head_dim, const LaunchParams& p, size_t lds, hi
 hipError_t launch_lse(const LaunchParams& p, hipStream_t s);
 hipError_t launch_select(const LaunchParams& p, hipStream_t s);
 hipError_t launch_gather(const LaunchParams& p, int row_bytes, int r_max, hipStream_t s);
-unsigned fused_grid(const LaunchParams& p);
-size_t fused_lds_bytes(int head_dim, int rpad_max);
-hipError_t launch_fused_bf16(int head_dim, int nq, const LaunchParams& p, size_t lds, hipStream_t s);
-hipError_t set_max_lds_fused(size_t bytes);
-hipError_t fused_blocks_per_cu(int head_dim, int nq, size_t lds, int* blocks);
+hipError_t launch_step_bf16(int head_dim, const LaunchParams& p, size_t lds, int parts,
+                            hipStream_t s);
+hipError_t set_max_lds_step(size_t bytes);
 // Raise the dynamic-LDS limit of the scoring kernels of one dtype to `bytes`.
 hipError_t set_max_lds_bf16(size_t bytes);
 hipError_t set_max_lds_f32(size_t bytes);

@@ -42,9 +42,9 @@ __device__ __forceinline__ bool decode_slice(const LaunchParams& prm, int& p, in
 }
 
 // Key blocks [b0, b1) of slice `slice` of a problem with N keys.
-__device__ __forceinline__ void slice_blocks(int N, int slice, int& b0, int& b1) {
+__device__ __forceinline__ void slice_blocks(int N, int S, int slice, int& b0, int& b1) {
   const int nb = (N + 31) >> 5;
-  const int per = (nb + stream_slices(N) - 1) / stream_slices(N);
+  const int per = (nb + S - 1) / S;
   b0 = slice * per;
   b1 = min(nb, b0 + per);
 }
@@ -60,9 +60,9 @@ __global__ __launch_bounds__(kThreads, 4) void rowstats_bf16(LaunchParams prm) {
   if (!decode_slice(prm, p, slice)) return;
   const finch_problem pb = prm.probs[p];
   const int N = pb.c + pb.m;
-  if (N == 0 || slice >= stream_slices(N)) return;
+  if (N == 0 || slice >= stream_slices(N, prm.slice_keys)) return;
   int b0, b1;
-  slice_blocks(N, slice, b0, b1);
+  slice_blocks(N, stream_slices(N, prm.slice_keys), slice, b0, b1);
   const int R = prm.group * pb.n_que;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int t = lane & 31, h = lane >> 5;
@@ -169,9 +169,9 @@ __global__ __launch_bounds__(kThreads, 4) void colsum_bf16(LaunchParams prm) {
   if (!decode_slice(prm, p, slice)) return;
   const finch_problem pb = prm.probs[p];
   const int N = pb.c + pb.m;
-  if (N == 0 || slice >= stream_slices(N)) return;
+  if (N == 0 || slice >= stream_slices(N, prm.slice_keys)) return;
   int b0, b1;
-  slice_blocks(N, slice, b0, b1);
+  slice_blocks(N, stream_slices(N, prm.slice_keys), slice, b0, b1);
   const int R = prm.group * pb.n_que;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int t = lane & 31, h = lane >> 5;
@@ -237,7 +237,7 @@ __global__ __launch_bounds__(256) void lse_merge(LaunchParams prm) {
   const int R = prm.group * pb.n_que;
   const int slices = N == 0 ? 0
                      : prm.tile_keys ? (N + prm.tile_keys - 1) / prm.tile_keys
-                                     : stream_slices(N);
+                                     : stream_slices(N, prm.slice_keys);
   const int rpad = round_up32(R);
   const float2* st = prm.stats + static_cast<size_t>(p) * prm.tiles_max * prm.rpad_max;
   float* lse = prm.lse + static_cast<size_t>(p) * prm.rpad_max;

@@ -59,15 +59,15 @@ def _which_scoring_kernels(fin, batch):
     return {k for k, v in prof.items() if v["launches"]}
 
 
-@pytest.mark.parametrize("d,group,path", [(128, 4, "fused"), (128, 4, "two_pass"), (64, 2, "fused"),
-                                          (128, 1, "fused"), (64, 8, "two_pass")])
-def test_both_scoring_paths(d, group, path):
-    """The single-pass (row statistics exchanged between workgroups) and the two-pass
-    scoring kernels, each forced, on the same ragged batch with up to 256 stacked rows."""
-    say(f"both_scoring_paths d={d} G={group} {path}")
+@pytest.mark.parametrize("d,group,path", [(128, 4, "fused"), (128, 4, "separate"), (64, 2, "fused"),
+                                          (128, 1, "fused"), (64, 8, "separate")])
+def test_both_step_paths(d, group, path):
+    """One kernel per step (work items handing results to each other through device
+    memory) and one kernel per stage, each forced, on the same ragged batch."""
+    say(f"both_step_paths d={d} G={group} {path}")
     fin = F.Finch(F.FINCH_BF16, d, group)
-    fin.set_scoring_path(F.FINCH_SCORING_FUSED if path == "fused" else F.FINCH_SCORING_TWO_PASS)
-    cap = 256 // group
+    fin.set_step_path(F.FINCH_PATH_FUSED if path == "fused" else F.FINCH_PATH_SEPARATE)
+    cap = 448 // group
     specs = [dict(s, n_que=min(s["n_que"], cap)) for s in RAGGED_SPECS]
     specs += [dict(n_que=cap, c=1364, m=4096, r=1408), dict(n_que=max(1, cap // 3), c=5, m=130, r=64)]
     batch, ts = H.single_step_case(fin, specs, torch.bfloat16, d, group, seed=300 + d + group)
@@ -76,7 +76,7 @@ def test_both_scoring_paths(d, group, path):
     say(f"  worst score rel err {st['worst_rel']:.2e}, near-tie swaps {st['swaps']}")
     assert fin.check() == 0
     ran = _which_scoring_kernels(fin, batch)
-    assert ("fused_score" in ran) == (path == "fused") and ("colsum" in ran) == (path != "fused"), ran
+    assert ran == ({"step"} if path == "fused" else {"rowstats", "lse", "colsum", "select", "gather"}), ran
     # a second launch on the same context: the synchronisation words were left clean
     for t in ts:
         t["scores"].fill_(-5.0)
@@ -88,13 +88,13 @@ def test_both_scoring_paths(d, group, path):
 
 def test_forced_fused_rejects_unsupported_batches():
     fin = F.Finch(F.FINCH_BF16, 128, 4)
-    fin.set_scoring_path(F.FINCH_SCORING_FUSED)
+    fin.set_step_path(F.FINCH_PATH_FUSED)
     batch, ts = H.single_step_case(fin, [dict(n_que=128, c=10, m=100, r=5)], torch.bfloat16, 128, 4, 1)
     with pytest.raises(F.FinchError) as e:
         fin.step(batch)
     assert e.value.status == F.FINCH_ERR_UNSUPPORTED
-    fin.set_scoring_path(F.FINCH_SCORING_AUTO)
-    fin.step(batch)                       # falls back to the two-pass kernels
+    fin.set_step_path(F.FINCH_PATH_AUTO)
+    fin.step(batch)                       # falls back to one kernel per stage
     H.validate_single_step(ts, "auto fallback")
     fin.close()
 
@@ -105,7 +105,7 @@ def test_abandoned_wait_is_reported_and_recoverable():
     the normal limit is correct again."""
     say("abandoned wait")
     fin = F.Finch(F.FINCH_BF16, 128, 4)
-    fin.set_scoring_path(F.FINCH_SCORING_FUSED)
+    fin.set_step_path(F.FINCH_PATH_FUSED)
     specs = [dict(n_que=48, c=1364, m=4096, r=1408)] * 24
     batch, ts = H.single_step_case(fin, specs, torch.bfloat16, 128, 4, seed=12)
     F.finch_set_option(fin.ctx, F.FINCH_OPT_SPIN_LIMIT, 1)
