@@ -56,6 +56,49 @@ __device__ __forceinline__ void load_k_block(const finch_problem& pb, int N, int
   }
 }
 
+// Values that are the same in every lane, moved into scalar registers (used where
+// the compiler cannot see the uniformity, e.g. arguments of non-inlined functions).
+__device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
+__device__ __forceinline__ float uni(float x) {
+  return __uint_as_float(static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(__float_as_uint(x)))));
+}
+template <typename T>
+__device__ __forceinline__ T* uni(T* p) {
+  const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+  const unsigned lo = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(v)));
+  const unsigned hi = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(v >> 32)));
+  return reinterpret_cast<T*>((static_cast<unsigned long long>(hi) << 32) | lo);
+}
+
+// Where the keys of a problem live: rows [0, c) in `cache`, the rest in `chunk`.
+struct KeySource {
+  const char* cache;
+  const char* chunk;
+  int c;
+};
+
+// load_k_block with the three descriptor fields it needs passed directly.
+template <int D>
+__device__ __forceinline__ void load_k_block(const KeySource& ks, int N, int kbase, int lane,
+                                             bf16x8 (&kf)[D / 16]) {
+  const int key = kbase + (lane & 31);
+  const int h = lane >> 5;
+  if (key < N) {
+    const char* row = key < ks.c ? ks.cache + static_cast<size_t>(key) * (D * 2)
+                                 : ks.chunk + static_cast<size_t>(key - ks.c) * (D * 2);
+    const FINCH_GLOBAL u32x4* rp = as_global<u32x4>(row);
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) {
+      const u32x4 raw = rp[2 * s + h];
+      kf[s] = __builtin_bit_cast(bf16x8, raw);
+    }
+  } else {
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) kf[s] = __builtin_bit_cast(bf16x8, zero);
+  }
+}
+
 // Copy prompt rows [row0, row0+rows) into LDS, rows past R as zeros.  Row stride
 // D*2+16 bytes keeps the 16-byte B-operand reads of 8 consecutive lanes on
 // distinct banks.  NT = threads of the workgroup.

@@ -229,18 +229,28 @@ struct ItemCtx {
 // register allocation; they are called once per workgroup.
 template <int D, int QBT>
 __device__ __attribute__((noinline)) void pass1_item(const LaunchParams& prm, const finch_problem& pb,
-                                                     const ItemCtx& c, char* smem, int* sh_word) {
+                                                     const ItemCtx& c) {
+  extern __shared__ __align__(16) char smem[];  // named here so that accesses stay LDS accesses
+  __shared__ int sh_flag;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int t = lane & 31, h = lane >> 5;
   constexpr int kStride = D * 2 + 16;
+  // arguments arrive through memory: pull what the loops use into scalar registers
+  const int rpad_max = uni(prm.rpad_max);
+  const float sc = uni(prm.scale_log2);
+  const int N = uni(c.N), QB = uni(c.QB), b1 = uni(c.b1), S = uni(c.S), R = uni(c.R),
+            rows = uni(c.rows), slice = uni(c.slice);
+  const KeySource ks = {uni(static_cast<const char*>(pb.k_cache)),
+                        uni(static_cast<const char*>(pb.k_chunk)), uni(pb.c)};
+  unsigned* arr = uni(c.arr);
+  float* glse = uni(c.glse);
+  float2* gstats = uni(c.gstats);
   char* lds_q = smem;
-  float2* wstats = reinterpret_cast<float2*>(smem + prm.rpad_max * kStride);  // [kWaves][rpad_max]
-  const float sc = prm.scale_log2;
-  const int N = c.N, QB = c.QB, b1 = c.b1;
+  float2* wstats = reinterpret_cast<float2*>(smem + rpad_max * kStride);  // [kWaves][rpad_max]
   bf16x8 ka[D / 16], kb[D / 16];
-  int b = c.b0 + wave;
-  if (b < b1) load_k_block<D>(pb, N, b << 5, lane, ka);  // requested before Q is staged
-  stage_q<D, kThreads>(pb.q, c.R, 0, c.rows, lds_q, tid);
+  int b = uni(c.b0) + wave;
+  if (b < b1) load_k_block<D>(ks, N, b << 5, lane, ka);  // requested before Q is staged
+  stage_q<D, kThreads>(uni(pb.q), R, 0, rows, lds_q, tid);
   __syncthreads();
   float m_run[QBT], z_run[QBT];
 #pragma unroll
@@ -281,11 +291,11 @@ __device__ __attribute__((noinline)) void pass1_item(const LaunchParams& prm, co
   };
   if (b < b1) {
     while (true) {
-      if (b + kWaves < b1) load_k_block<D>(pb, N, (b + kWaves) << 5, lane, kb);
+      if (b + kWaves < b1) load_k_block<D>(ks, N, (b + kWaves) << 5, lane, kb);
       process(ka, b);
       b += kWaves;
       if (b >= b1) break;
-      if (b + kWaves < b1) load_k_block<D>(pb, N, (b + kWaves) << 5, lane, ka);
+      if (b + kWaves < b1) load_k_block<D>(ks, N, (b + kWaves) << 5, lane, ka);
       process(kb, b);
       b += kWaves;
       if (b >= b1) break;
@@ -298,71 +308,83 @@ __device__ __attribute__((noinline)) void pass1_item(const LaunchParams& prm, co
       const float m2 = __shfl_xor(m, 32);
       const float z2 = __shfl_xor(z, 32);
       merge_stats(m, z, m2, z2);
-      if (h == 0) wstats[wave * prm.rpad_max + q * 32 + t] = make_float2(m, z);
+      if (h == 0) wstats[wave * rpad_max + q * 32 + t] = make_float2(m, z);
     }
   }
   __syncthreads();
-  float2* out = c.gstats + static_cast<size_t>(c.slice) * prm.rpad_max;
-  for (int i = tid; i < c.rows; i += kThreads) {
+  float2* out = gstats + static_cast<size_t>(slice) * rpad_max;
+  for (int i = tid; i < rows; i += kThreads) {
     float2 a = wstats[i];
 #pragma unroll
     for (int w = 1; w < kWaves; ++w) {
-      const float2 x = wstats[w * prm.rpad_max + i];
+      const float2 x = wstats[w * rpad_max + i];
       merge_stats(a.x, a.y, x.x, x.y);
     }
     st_stat(out + i, a.x, a.y);
   }
   stores_done();
   __syncthreads();
-  if (tid == 0) *sh_word = (add_u32(c.arr, 1u) == static_cast<unsigned>(c.S) - 1u) ? 1 : 0;
+  if (tid == 0) sh_flag = (add_u32(arr, 1u) == static_cast<unsigned>(S) - 1u) ? 1 : 0;
   __syncthreads();
-  if (__builtin_amdgcn_readfirstlane(*sh_word)) {
+  if (__builtin_amdgcn_readfirstlane(sh_flag)) {
     // last slice of the problem: merge the slices (fixed order) and publish lse
-    for (int i = tid; i < c.rows; i += kThreads) {
+    for (int i = tid; i < rows; i += kThreads) {
       float l = kInf;  // padding rows add exp2(-inf) = 0 in pass 2
-      if (i < c.R) {
+      if (i < R) {
         float m = -kInf, z = 0.f;
-        for (int sl = 0; sl < c.S; ++sl) {
-          const float2 s2 = ld_stat(c.gstats + static_cast<size_t>(sl) * prm.rpad_max + i);
+        for (int sl = 0; sl < S; ++sl) {
+          const float2 s2 = ld_stat(gstats + static_cast<size_t>(sl) * rpad_max + i);
           merge_stats(m, z, s2.x, s2.y);
         }
         l = m + fast_log2(z);
       }
-      st_f32(c.glse + i, l);
+      st_f32(glse + i, l);
     }
     stores_done();
     __syncthreads();
-    if (tid == 0) add_u32(c.arr, 1u);  // S + 1: lse is out
+    if (tid == 0) add_u32(arr, 1u);  // S + 1: lse is out
   }
 }
 
 // Returns (uniformly) whether this workgroup finished the last pass-2 slice.
 template <int D>
 __device__ __attribute__((noinline)) int pass2_item(const LaunchParams& prm, const finch_problem& pb,
-                                                    const ItemCtx& c, char* smem, int* sh_word) {
+                                                    const ItemCtx& c) {
+  extern __shared__ __align__(16) char smem[];
+  __shared__ int sh_flag;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int t = lane & 31, h = lane >> 5;
   constexpr int kStride = D * 2 + 16;
+  // arguments arrive through memory: pull what the loops use into scalar registers
+  const int rpad_max = uni(prm.rpad_max);
+  const float sc = uni(prm.scale_log2);
+  const unsigned spin_limit = static_cast<unsigned>(uni(static_cast<int>(prm.spin_limit)));
+  const int N = uni(c.N), QB = uni(c.QB), b1 = uni(c.b1), S = uni(c.S), R = uni(c.R),
+            rows = uni(c.rows);
+  const KeySource ks = {uni(static_cast<const char*>(pb.k_cache)),
+                        uni(static_cast<const char*>(pb.k_chunk)), uni(pb.c)};
+  unsigned* arr = uni(c.arr);
+  float* glse = uni(c.glse);
+  float* gscores = uni(c.gscores);
+  unsigned* sync = uni(prm.sync);
   char* lds_q = smem;
-  float* lds_lse = reinterpret_cast<float*>(smem + prm.rpad_max * kStride);
-  const float sc = prm.scale_log2;
-  const int N = c.N, QB = c.QB, b1 = c.b1;
+  float* lds_lse = reinterpret_cast<float*>(smem + rpad_max * kStride);
   bf16x8 ka[D / 16], kb[D / 16];
-  int b = c.b0 + wave;
-  if (b < b1) load_k_block<D>(pb, N, b << 5, lane, ka);
-  stage_q<D, kThreads>(pb.q, c.R, 0, c.rows, lds_q, tid);
+  int b = uni(c.b0) + wave;
+  if (b < b1) load_k_block<D>(ks, N, b << 5, lane, ka);
+  stage_q<D, kThreads>(uni(pb.q), R, 0, rows, lds_q, tid);
   if (tid == 0) {  // wait for the problem's lse (written by items with smaller tickets)
     unsigned spins = 0;
-    while (ld_u32(c.arr) <= static_cast<unsigned>(c.S)) {
+    while (ld_u32(arr) <= static_cast<unsigned>(S)) {
       __builtin_amdgcn_s_sleep(4);
-      if (++spins > prm.spin_limit) {
-        __hip_atomic_fetch_or(&prm.sync[kSyncError], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (++spins > spin_limit) {
+        __hip_atomic_fetch_or(&sync[kSyncError], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         break;
       }
     }
   }
   __syncthreads();
-  for (int i = tid; i < c.rows; i += kThreads) lds_lse[i] = ld_f32(c.glse + i);
+  for (int i = tid; i < rows; i += kThreads) lds_lse[i] = ld_f32(glse + i);
   __syncthreads();
   auto process = [&](const bf16x8(&kf)[D / 16], int blk) {
     const int kbase = blk << 5;
@@ -379,15 +401,15 @@ __device__ __attribute__((noinline)) int pass2_item(const LaunchParams& prm, con
     }
     const float tot = fold16_over32(u, t);
     const int key = kbase + acc_key(t >> 1, h);
-    if ((t & 1) == 0 && key < N) st_f32(c.gscores + key, tot);
+    if ((t & 1) == 0 && key < N) st_f32(gscores + key, tot);
   };
   if (b < b1) {
     while (true) {
-      if (b + kWaves < b1) load_k_block<D>(pb, N, (b + kWaves) << 5, lane, kb);
+      if (b + kWaves < b1) load_k_block<D>(ks, N, (b + kWaves) << 5, lane, kb);
       process(ka, b);
       b += kWaves;
       if (b >= b1) break;
-      if (b + kWaves < b1) load_k_block<D>(pb, N, (b + kWaves) << 5, lane, ka);
+      if (b + kWaves < b1) load_k_block<D>(ks, N, (b + kWaves) << 5, lane, ka);
       process(kb, b);
       b += kWaves;
       if (b >= b1) break;
@@ -395,14 +417,15 @@ __device__ __attribute__((noinline)) int pass2_item(const LaunchParams& prm, con
   }
   stores_done();
   __syncthreads();
-  if (tid == 0) *sh_word = (add_u32(c.arr + 1, 1u) == static_cast<unsigned>(c.S) - 1u) ? 1 : 0;
+  if (tid == 0) sh_flag = (add_u32(arr + 1, 1u) == static_cast<unsigned>(S) - 1u) ? 1 : 0;
   __syncthreads();
-  return __builtin_amdgcn_readfirstlane(*sh_word);
+  return __builtin_amdgcn_readfirstlane(sh_flag);
 }
 
 // Top-r of one problem whose scores are all out; idx goes to memory.
 __device__ __attribute__((noinline)) void select_item(const LaunchParams& prm, const finch_problem& pb,
-                                                      const ItemCtx& c, char* smem) {
+                                                      const ItemCtx& c) {
+  extern __shared__ __align__(16) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int N = c.N;
   const int r = min(pb.r, N);
@@ -461,7 +484,6 @@ __device__ __attribute__((noinline)) void gather_item(const LaunchParams& prm, c
 // items per problem (0: scoring only, nothing after pass 2).
 template <int D, int QBT>
 __global__ __launch_bounds__(kThreads, 4) void step_bf16(LaunchParams prm, int n1, int parts) {
-  extern __shared__ __align__(16) char smem[];
   __shared__ int sh_word;
   const int tid = threadIdx.x;
   unsigned* sync = prm.sync;
@@ -496,13 +518,13 @@ __global__ __launch_bounds__(kThreads, 4) void step_bf16(LaunchParams prm, int n
     c.gscores = pb.scores ? pb.scores : prm.ws_scores + static_cast<size_t>(c.p) * prm.score_stride;
     if (phase == 0) {
       slice_blocks(c.N, c.S, c.slice, c.b0, c.b1);
-      pass1_item<D, QBT>(prm, pb, c, smem, &sh_word);
+      pass1_item<D, QBT>(prm, pb, c);
     } else if (phase == 1) {
       slice_blocks(c.N, c.S, c.slice, c.b0, c.b1);
-      if (pass2_item<D>(prm, pb, c, smem, &sh_word)) {
+      if (pass2_item<D>(prm, pb, c)) {
         // last slice of the problem: every score of the problem is out
         if (parts > 0) {
-          select_item(prm, pb, c, smem);
+          select_item(prm, pb, c);
           stores_done();
           __syncthreads();
           if (tid == 0) add_u32(c.arr + 1, 1u);  // S + 1: the indices are out
