@@ -59,9 +59,9 @@ inline bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
 size_t score_lds(const finch_ctx* ctx, int row_chunk) {
   const size_t d = static_cast<size_t>(ctx->cfg.head_dim);
   // per staged row: the row itself + one (max,sum) pair per wave (pass 1), which
-  // also covers the 4-byte lse entry of pass 2
+  // also covers the 4-byte lse entry of pass 2; then 16 bytes for the key-block counter
   if (ctx->cfg.dtype == FINCH_BF16)
-    return static_cast<size_t>(row_chunk) * (d * 2 + 16 + (finch::kStreamThreads / 64) * sizeof(float2));
+    return static_cast<size_t>(row_chunk) * (d * 2 + 16 + (finch::kStreamThreads / 64) * sizeof(float2)) + 16;
   return static_cast<size_t>(row_chunk) * (d * 4 + 4 * sizeof(float2));
 }
 
@@ -182,6 +182,7 @@ LaunchParams make_params(const finch_ctx* ctx, const finch_problem* dd, int32_t 
   p.tiles_max = pl.tiles_max;
   p.tile_keys = ctx->cfg.dtype == FINCH_BF16 ? 0 : finch::kTileKeys;
   p.slice_keys = ctx->slice_keys;
+  p.merge_in_pass2 = (ctx->cfg.dtype == FINCH_BF16 && pl.tiles_max <= 16) ? 1 : 0;
   p.rpad_max = pl.rpad_max;
   p.row_chunk = pl.row_chunk;
   p.score_stride = pl.score_stride;
@@ -241,7 +242,7 @@ finch_status run_score(finch_ctx* ctx, const LaunchParams& p, const Plan& pl, hi
              : finch::launch_rowstats_f32(d, p, pl.lds_bytes, s);
   }
   if (e != hipSuccess) return hip_fail(ctx, e);
-  {
+  if (!p.merge_in_pass2) {
     ProfScope ps(ctx, FINCH_KERNEL_LSE, s);
     e = finch::launch_lse(p, s);
   }

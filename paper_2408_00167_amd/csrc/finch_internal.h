@@ -45,6 +45,7 @@ struct LaunchParams {
                                // tile_keys == 0
   int32_t tile_keys;           // kTileKeys for the fp32 kernels, 0 for the bf16 ones
   int32_t slice_keys;          // target keys per slice of the bf16 kernels
+  int32_t merge_in_pass2;      // bf16: pass 2 merges the slice statistics itself (no lse kernel)
   int32_t rpad_max;            // max_p round_up(G*n_que, 32)
   int32_t row_chunk;           // rows staged per pass over the keys (multiple of 32)
   int32_t score_stride;        // floats per problem in ws_scores

@@ -49,6 +49,14 @@ __device__ __forceinline__ void slice_blocks(int N, int S, int slice, int& b0, i
   b1 = min(nb, b0 + per);
 }
 
+// Next key block of the slice for this wave: the waves of a workgroup take blocks
+// from a shared LDS counter, so a wave that falls behind simply takes fewer.
+__device__ __forceinline__ int next_block(int* counter, int lane) {
+  int v = 0;
+  if (lane == 0) v = atomicAdd(counter, 1);
+  return __builtin_amdgcn_readfirstlane(v);
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------- pass 1
@@ -119,7 +127,8 @@ __global__ __launch_bounds__(kThreads, 4) void rowstats_bf16(LaunchParams prm) {
       }
     };
 
-    // key blocks of this wave, two register sets in ping-pong
+    // key blocks of this wave (a fixed assignment: the order in which a row's sums
+    // are added up must not depend on timing), two register sets in ping-pong
     bf16x8 ka[D / 16], kb[D / 16];
     int b = b0 + wave;
     if (b < b1) {
@@ -178,6 +187,7 @@ __global__ __launch_bounds__(kThreads, 4) void colsum_bf16(LaunchParams prm) {
   constexpr int kStride = D * 2 + 16;
   char* lds_q = smem;
   float* lds_lse = reinterpret_cast<float*>(smem + prm.row_chunk * kStride);
+  int* sh_next = reinterpret_cast<int*>(smem + prm.row_chunk * (kStride + kWaves * 8));
   const float* lse = prm.lse + static_cast<size_t>(p) * prm.rpad_max;
   const float sc = prm.scale_log2;
   FINCH_GLOBAL float* dst = as_global_mut<float>(
@@ -188,7 +198,27 @@ __global__ __launch_bounds__(kThreads, 4) void colsum_bf16(LaunchParams prm) {
     const int QB = rows >> 5;
     const bool first_chunk = row0 == 0;
     stage_q<D, kThreads>(pb.q, R, row0, rows, lds_q, tid);
-    for (int i = tid; i < rows; i += kThreads) lds_lse[i] = lse[row0 + i];
+    if (tid == 0) *sh_next = 0;
+    if (prm.merge_in_pass2) {
+      // few slices: merge their statistics here (same order as lse_merge) instead
+      // of spending a kernel launch on it
+      const int S = stream_slices(N, prm.slice_keys);
+      const float2* st = prm.stats + static_cast<size_t>(p) * prm.tiles_max * prm.rpad_max;
+      for (int i = tid; i < rows; i += kThreads) {
+        float l = kInf;
+        if (row0 + i < R) {
+          float m = -kInf, z = 0.f;
+          for (int sl = 0; sl < S; ++sl) {
+            const float2 s2 = st[static_cast<size_t>(sl) * prm.rpad_max + row0 + i];
+            merge_stats(m, z, s2.x, s2.y);
+          }
+          l = m + fast_log2(z);
+        }
+        lds_lse[i] = l;
+      }
+    } else {
+      for (int i = tid; i < rows; i += kThreads) lds_lse[i] = lse[row0 + i];
+    }
     __syncthreads();
 
     auto process = [&](const bf16x8(&kf)[D / 16], int b) {
@@ -209,18 +239,22 @@ __global__ __launch_bounds__(kThreads, 4) void colsum_bf16(LaunchParams prm) {
       if ((t & 1) == 0 && key < N) dst[key] = first_chunk ? tot : dst[key] + tot;
     };
 
+    // key blocks are handed out by the workgroup's counter (each key's sum is
+    // computed by one wave, so the result does not depend on who takes which)
     bf16x8 ka[D / 16], kb[D / 16];
-    int b = b0 + wave;
+    int b = b0 + next_block(sh_next, lane);
     if (b < b1) {
       load_k_block<D>(pb, N, b << 5, lane, ka);
       while (true) {
-        if (b + kWaves < b1) load_k_block<D>(pb, N, (b + kWaves) << 5, lane, kb);
+        int bn = b0 + next_block(sh_next, lane);
+        if (bn < b1) load_k_block<D>(pb, N, bn << 5, lane, kb);
         process(ka, b);
-        b += kWaves;
+        b = bn;
         if (b >= b1) break;
-        if (b + kWaves < b1) load_k_block<D>(pb, N, (b + kWaves) << 5, lane, ka);
+        bn = b0 + next_block(sh_next, lane);
+        if (bn < b1) load_k_block<D>(pb, N, bn << 5, lane, ka);
         process(kb, b);
-        b += kWaves;
+        b = bn;
         if (b >= b1) break;
       }
     }

@@ -76,7 +76,7 @@ def test_both_step_paths(d, group, path):
     say(f"  worst score rel err {st['worst_rel']:.2e}, near-tie swaps {st['swaps']}")
     assert fin.check() == 0
     ran = _which_scoring_kernels(fin, batch)
-    assert ran == ({"step"} if path == "fused" else {"rowstats", "lse", "colsum", "select", "gather"}), ran
+    assert ran == ({"step"} if path == "fused" else {"rowstats", "colsum", "select", "gather"}), ran
     # a second launch on the same context: the synchronisation words were left clean
     for t in ts:
         t["scores"].fill_(-5.0)
@@ -160,6 +160,22 @@ def test_many_prompt_rows_are_chunked():
     fin.step(batch)
     st = H.validate_single_step(ts, "R=640")
     say(f"  worst score rel err {st['worst_rel']:.2e}")
+    fin.close()
+
+
+def test_many_slices_use_the_merge_kernel():
+    """More than 16 key slices per problem: the slice statistics are merged by a
+    kernel of their own instead of by pass 2."""
+    say("many_slices")
+    fin = F.Finch(F.FINCH_BF16, 128, 4)
+    F.finch_set_option(fin.ctx, F.FINCH_OPT_SLICE_KEYS, 256)
+    specs = [dict(n_que=40, c=1000, m=4200, r=333), dict(n_que=3, c=0, m=290, r=20),
+             dict(n_que=40, c=17, m=0, r=4)]
+    batch, ts = H.single_step_case(fin, specs, torch.bfloat16, 128, 4, seed=11)
+    fin.step(batch)
+    st = H.validate_single_step(ts, "20 slices")
+    say(f"  worst score rel err {st['worst_rel']:.2e}")
+    assert _which_scoring_kernels(fin, batch) == {"rowstats", "lse", "colsum", "select", "gather"}
     fin.close()
 
 
