@@ -22,6 +22,18 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+COPY_CALIBRATION_BYTES = 1 << 30
+
+# HBM bytes per launch from hardware counters (two rocprofv3 --pmc runs of this
+# program on C4, FETCH_SIZE then WRITE_SIZE, each scaled by what the same counter
+# reads for the 1 GiB elementwise copy of --copy-calibration).  Offline figures:
+# bench.py cannot read counters itself.  None = not measured for that kernel/workload.
+MEASURED_TRAFFIC = {"C4": {
+    "rowstats": 2.0 * 159449.5 * 1024 + 768.0 * 1024,
+    "colsum": 2.0 * 159521.3 * 1024 + 4780.0 * 1024,
+    "select": 2.0 * 2464.5 * 1024 + 728.0 * 1024,
+    "gather": 2.0 * 47121.8 * 1024 + 92928.0 * 1024,
+}}
 
 
 def algorithmic_bytes(w, loop):
@@ -43,27 +55,30 @@ def algorithmic_bytes(w, loop):
     return per, total, keys
 
 
-def cpu_baseline(w, probs_cpu, chunk, budget_s=20.0):
-    """The oracle, as it stands, on the host cores: whole chunk loops of a few
-    sampled problems, extrapolated linearly to the whole job."""
+def cpu_baseline(w, next_problem, chunk, budget_s=15.0):
+    """The oracle, as it stands, on the host cores: whole chunk loops of sampled
+    problems (drawn one at a time from `next_problem` until about `budget_s` seconds
+    of oracle time have been spent), extrapolated linearly to the whole job."""
     from oracle import finch_oracle as O
     try:
         from threadpoolctl import threadpool_info
         cores = max([int(x.get("num_threads", 1)) for x in threadpool_info()] + [1])
     except Exception:
         cores = 1
-    done, t0 = 0, time.perf_counter()
-    for pb in probs_cpu:
-        O.compress(pb["Q"], pb["K"], pb["V"], chunk, pb["budget"])
-        done += 1
-        if time.perf_counter() - t0 > budget_s:
+    done, dt = 0, 0.0
+    while dt < budget_s and done < w.n_problems:
+        pb = next_problem(done)
+        if pb is None:
             break
-    dt = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        O.compress(pb["Q"], pb["K"], pb["V"], chunk, pb["budget"])
+        dt += time.perf_counter() - t0
+        done += 1
     n_tokens = sum(r.n_cont for r in w.requests)
     whole_job_s = dt / done * w.n_problems
     return dict(value=n_tokens / whole_job_s, unit="document tokens/s", cores=cores, kind="oracle",
-                sample=(f"{done} of {w.n_problems} problems of {w.name} (request 0, layer 0), full "
-                        f"chunk loop each, {dt:.1f} s measured, extrapolated linearly to all problems"))
+                sample=(f"{done} of {w.n_problems} problems of {w.name} (in workload order), full "
+                        f"chunk loop each, {dt:.1f} s of oracle time, extrapolated linearly to all problems"))
 
 
 def main() -> int:
@@ -74,6 +89,9 @@ def main() -> int:
     ap.add_argument("--workload", default="C4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain elementwise copy of 1 GiB (read 1 GiB, write 1 GiB) three "
+                         "times, so that a counter run of this command holds a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (problems are independent; there is no "
@@ -123,6 +141,14 @@ def main() -> int:
     ev_ms = ev0.elapsed_time(ev1) / args.steps
     ms = wall_ms
 
+    if args.copy_calibration:
+        src = torch.ones(COPY_CALIBRATION_BYTES // 4, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+
     # Per-kernel durations: the same loop again with HIP events around every launch
     # (on the launch stream).  Kept out of the pass that produced `value` because the
     # event records themselves lengthen the loop.
@@ -152,7 +178,8 @@ def main() -> int:
         bytes_per_launch = per_kernel_bytes[klass] / launches
         achieved = bytes_per_launch / (kernels[dom]["avg_us"] * 1e-6) / 1e9
         roofline = dict(bound="hbm", kernel=dom, achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s",
-                        frac=achieved / HBM_PEAK_GBPS, traffic=None,
+                        frac=achieved / HBM_PEAK_GBPS,
+                        traffic=MEASURED_TRAFFIC.get(w.name, {}).get(dom),
                         bytes_per_launch=bytes_per_launch, avg_launch_us=kernels[dom]["avg_us"],
                         launches_per_step=launches, profiled_ms_per_step=prof_ms)
 
@@ -177,13 +204,17 @@ def main() -> int:
         "setup_s": t_gen,
     }
     if not args.no_cpu_baseline:
-        sample = []
-        b0 = 0
-        for g in range(min(w.kv_heads, 8)):
-            p = W.make_problem(w, b0, 0, g, device=dev)
-            sample.append(dict(Q=W.to_numpy_storage(p["Q"]), K=W.to_numpy_storage(p["K"]),
-                               V=W.to_numpy_storage(p["V"]), budget=w.requests[b0].budget))
-        out["cpu_baseline"] = cpu_baseline(w, sample, w.chunk)
+        order = list(W.problems_of(w))
+
+        def next_problem(i):
+            if i >= len(order):
+                return None
+            b, l, g = order[i]
+            p = W.make_problem(w, b, l, g, device=dev)
+            return dict(Q=W.to_numpy_storage(p["Q"]), K=W.to_numpy_storage(p["K"]),
+                        V=W.to_numpy_storage(p["V"]), budget=w.requests[b].budget)
+
+        out["cpu_baseline"] = cpu_baseline(w, next_problem, w.chunk)
     print(json.dumps(out), flush=True)
     fin.close()
     return 0
