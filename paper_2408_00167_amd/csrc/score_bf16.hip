@@ -93,6 +93,10 @@ __global__ __launch_bounds__(kThreads, 4) void rowstats_bf16(LaunchParams prm) {
       z_run[q] = 0.f;
     }
 
+    // The running reference m_run of a row only has to keep exp2 in range, so it is
+    // taken from the wave's first key block and moved (with the sum rescaled) only
+    // when a block's sum shows that its logits lie far above it.
+    bool seeded = false;
     auto process = [&](const bf16x8(&kf)[D / 16], int b) {
       const int kbase = b << 5;
       const bool ragged = kbase + 32 > N;
@@ -107,24 +111,32 @@ __global__ __launch_bounds__(kThreads, 4) void rowstats_bf16(LaunchParams prm) {
             for (int v = 0; v < 16; ++v)
               if (kbase + acc_key(v, h) >= N) a[v] = -kInf;
           }
-          float bm = fmaxf(a[0], a[1]);
+          float z = 0.f;
+          bool move = !seeded;
+          if (seeded) {
+            const float mu = (m_run[q] == -kInf) ? 0.f : m_run[q];
 #pragma unroll
-          for (int v = 2; v < 16; v += 2) bm = fmaxf(fmaxf(bm, a[v]), a[v + 1]);
-          const float bms = bm * sc;
-          if (__any(bms > m_run[q])) {  // rare after the first blocks: rescale the running sum
-            const float mn = fmaxf(m_run[q], bms);
-            // exp2(-inf) = 0 on a lane's first block; a lane-half that has seen only
-            // masked keys so far (mn still -inf) keeps its empty sum
+            for (int v = 0; v < 16; ++v) z += fast_exp2(__builtin_fmaf(a[v], sc, -mu));
+            move = __any(!(z <= 0x1p64f));
+          }
+          if (move) {
+            float bm = fmaxf(a[0], a[1]);
+#pragma unroll
+            for (int v = 2; v < 16; v += 2) bm = fmaxf(fmaxf(bm, a[v]), a[v + 1]);
+            const float mn = fmaxf(m_run[q], bm * sc);
+            // a lane half that has seen only masked keys so far (mn still -inf) keeps
+            // its empty sum
             z_run[q] = (mn == -kInf) ? 0.f : z_run[q] * fast_exp2(m_run[q] - mn);
             m_run[q] = mn;
-          }
-          const float mu = (m_run[q] == -kInf) ? 0.f : m_run[q];
-          float z = 0.f;
+            const float mu = (mn == -kInf) ? 0.f : mn;
+            z = 0.f;
 #pragma unroll
-          for (int v = 0; v < 16; ++v) z += fast_exp2(__builtin_fmaf(a[v], sc, -mu));
+            for (int v = 0; v < 16; ++v) z += fast_exp2(__builtin_fmaf(a[v], sc, -mu));
+          }
           z_run[q] += z;
         }
       }
+      seeded = true;
     };
 
     // key blocks of this wave (a fixed assignment: the order in which a row's sums

@@ -133,6 +133,10 @@ def single_step_case(fin: F.Finch, specs: Sequence[Dict], dtype: torch.dtype, d:
             scores=None if null_scores else torch.full((max(N, 1) + 1,), -5.0, device="cuda"),
             idx=torch.full((max(rr, 1) + 1,), -9, dtype=torch.int32, device="cuda"),
             n_que=sp["n_que"], c=c, m=m, r=r)
+        if "kramp" in sp and m > 0:
+            # key magnitudes change steadily along the chunk (from 1x to kramp x)
+            ramp = torch.logspace(0.0, float(np.log10(sp["kramp"])), m, device="cuda").unsqueeze(1)
+            t["k_chunk"] = (t["k_chunk"].float() * ramp).to(dtype)
         ts.append(t)
     descs = []
     for t in ts:

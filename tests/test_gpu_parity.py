@@ -196,6 +196,29 @@ def test_large_logits_do_not_overflow():
     fin.close()
 
 
+@pytest.mark.parametrize("kramp", [60.0, 1.0 / 60.0])
+def test_logits_far_from_the_first_blocks_reference(kramp):
+    """Key magnitudes rise (or fall) 60-fold along one slice, so the logits of later key
+    blocks lie hundreds of powers of two above (below) those of the blocks a wave
+    starts with: the reference of the running sums has to move (must not be needed)."""
+    say(f"logit ramp x{kramp:.3g}")
+    fin = F.Finch(F.FINCH_BF16, 128, 4)
+    specs = [dict(n_que=12, c=0, m=3000, r=100, qscale=4.0, kramp=kramp),
+             dict(n_que=40, c=10, m=2200, r=64, qscale=3.0, kramp=kramp)]
+    batch, ts = H.single_step_case(fin, specs, torch.bfloat16, 128, 4, seed=12)
+    fin.step(batch)
+    torch.cuda.synchronize()
+    for t in ts:
+        N, R = t["c"] + t["m"], 4 * t["n_que"]
+        got = t["scores"][:N].double().cpu().numpy()
+        want = O.key_scores(W.to_numpy_storage(t["q"]), W.to_numpy_storage(t["k_cache"]),
+                            W.to_numpy_storage(t["k_chunk"]))
+        assert np.isfinite(got).all() and abs(got.sum() - R) < 1e-3 * R
+        big = want > 1e-6
+        assert np.abs(got[big] - want[big]).max() / want[big].max() < 2e-3
+    fin.close()
+
+
 def test_scores_sum_to_number_of_rows_and_are_reproducible():
     say("scores_sum / reproducible")
     fin = F.Finch(F.FINCH_BF16, 128, 4)
