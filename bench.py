@@ -170,11 +170,11 @@ def main() -> int:
                 kernels[name] = dict(avg_us=1e3 * v["ms"] / v["launches"], launches_per_step=v["launches"] // prof_steps,
                                      ms_per_step=v["ms"] / prof_steps)
         dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
-        klass = {"rowstats": "score_pass", "colsum": "score_pass", "step": "step",
+        klass = {"rowstats": "score_pass", "colsum": "score_pass", "step": "step", "owner": "step",
                  "select": "select", "gather": "gather", "lse": "select"}[dom]
         launches = kernels[dom]["launches_per_step"]
         # the one-kernel-per-step launch moves everything the step has to move
-        per_kernel_bytes["step"] = per_kernel_bytes["score_pass"] + per_kernel_bytes["gather"]
+        per_kernel_bytes["step"] = 2 * per_kernel_bytes["score_pass"] + per_kernel_bytes["gather"]
         bytes_per_launch = per_kernel_bytes[klass] / launches
         achieved = bytes_per_launch / (kernels[dom]["avg_us"] * 1e-6) / 1e9
         roofline = dict(bound="hbm", kernel=dom, achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s",

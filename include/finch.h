@@ -110,6 +110,29 @@ finch_status finch_step(finch_ctx* ctx, const finch_problem* host_desc,
                         const finch_problem* dev_desc, int32_t n_problems,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/* The whole chunk loop in one call (Method: Document Segmentation - chunk after
+ * chunk, each step's kept pairs competing with the next chunk): the same results as
+ * finch_step on the batch of step 0, then on that of step 1, and so on.  The
+ * descriptors of step s are host_desc[step_first[s] .. step_first[s+1]) (dev_desc
+ * holds the same bytes on the device); step_first has n_steps + 1 entries, starts at
+ * 0, and the number of problems per step must not grow with s.  Slot j of every
+ * step in which it is present describes the same problem (normally its k_cache /
+ * v_cache at step s+1 are its k_out / v_out of step s), and no descriptor may read
+ * memory that a descriptor in another slot writes: slots are processed
+ * independently, each through all of its steps, possibly by one kernel launch for
+ * the whole loop (one workgroup per slot; picked under FINCH_PATH_AUTO when the
+ * slots fill the chip, forced by FINCH_PATH_OWNER), otherwise step by step.
+ * host_step_first is host memory, dev_step_first a device copy of it.  The
+ * workspace must hold finch_loop_workspace_size bytes (never more than
+ * finch_workspace_size of all descriptors taken as one batch). */
+finch_status finch_loop_workspace_size(const finch_ctx* ctx, const finch_problem* host_desc,
+                                       const int32_t* host_step_first, int32_t n_steps,
+                                       size_t* bytes);
+finch_status finch_loop(finch_ctx* ctx, const finch_problem* host_desc,
+                        const finch_problem* dev_desc, const int32_t* host_step_first,
+                        const int32_t* dev_step_first, int32_t n_steps, void* workspace,
+                        size_t workspace_bytes, void* stream);
+
 /* Host-only: rows kept after each chunk step (Method: the update rule
  * r_{it+1} = m_{it+1}/sigma + c_it with sigma = n_cont/k, ending at r = k), in
  * integers: r_i = min(c_{i-1} + m_i, floor(min(k, n_cont) * seen_i / n_cont)).
@@ -117,9 +140,13 @@ finch_status finch_step(finch_ctx* ctx, const finch_problem* host_desc,
 finch_status finch_schedule(int64_t n_cont, int32_t m, int64_t k, int32_t* r_out,
                             int32_t r_len);
 
-/* Options.  FINCH_OPT_STEP_PATH picks how the stages are launched.  SEPARATE, and
- * AUTO (default, = SEPARATE: it is the faster one on the measured workloads), use
+/* Options.  FINCH_OPT_STEP_PATH picks how the stages are launched.  SEPARATE uses
  * one kernel per stage: row statistics, merge, per-key sums, top-r, compaction.
+ * OWNER (bf16 only) gives every problem to one workgroup of 16 waves that runs all
+ * stages of the step - or, in finch_loop, of all steps - back to back with nothing
+ * exchanged between workgroups; batches it cannot run fail with
+ * FINCH_ERR_UNSUPPORTED.  AUTO (default) takes OWNER when the batch has enough
+ * problems to fill the chip's compute units in whole rounds, else SEPARATE.
  * FUSED runs finch_step (and finch_score) as ONE kernel when the batch allows it
  * (bf16, G*n_que <= 448; other batches fail with FINCH_ERR_UNSUPPORTED): its
  * workgroups take pass-1, pass-2, top-r and copy work items from a queue and hand
@@ -136,7 +163,12 @@ typedef enum {
    * streams (default 2400); a problem is cut into round((c+m)/value) slices */
   FINCH_OPT_SLICE_KEYS = 3
 } finch_option;
-typedef enum { FINCH_PATH_AUTO = 0, FINCH_PATH_SEPARATE = 1, FINCH_PATH_FUSED = 2 } finch_path;
+typedef enum {
+  FINCH_PATH_AUTO = 0,
+  FINCH_PATH_SEPARATE = 1,
+  FINCH_PATH_FUSED = 2,
+  FINCH_PATH_OWNER = 3
+} finch_path;
 finch_status finch_set_option(finch_ctx* ctx, int32_t option, int64_t value);
 
 /* Synchronises `stream`, then reports the context's device error word in
@@ -159,7 +191,8 @@ typedef enum {
   FINCH_KERNEL_SELECT = 3,   /* top-r                                        */
   FINCH_KERNEL_GATHER = 4,   /* compaction                                   */
   FINCH_KERNEL_STEP = 5,     /* all stages in one kernel (replaces 0..4)     */
-  FINCH_KERNEL_COUNT = 6
+  FINCH_KERNEL_OWNER = 6,    /* all stages, one workgroup per problem        */
+  FINCH_KERNEL_COUNT = 7
 } finch_kernel;
 finch_status finch_profile(finch_ctx* ctx, int32_t enable);
 finch_status finch_profile_read(finch_ctx* ctx, float* ms, int32_t* launches);

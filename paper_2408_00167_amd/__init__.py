@@ -30,10 +30,10 @@ EXPORTED_SYMBOLS = (
     "finch_create", "finch_destroy", "finch_workspace_size", "finch_score", "finch_topk",
     "finch_compact", "finch_step", "finch_schedule", "finch_last_hip_error",
     "finch_status_string", "finch_version", "finch_profile", "finch_profile_read",
-    "finch_set_option", "finch_check",
+    "finch_set_option", "finch_check", "finch_loop", "finch_loop_workspace_size",
 )
 
-KERNEL_NAMES = ("rowstats", "lse", "colsum", "select", "gather", "step")
+KERNEL_NAMES = ("rowstats", "lse", "colsum", "select", "gather", "step", "owner")
 
 FINCH_OPT_STEP_PATH = 1
 FINCH_OPT_SPIN_LIMIT = 2
@@ -41,6 +41,7 @@ FINCH_OPT_SLICE_KEYS = 3
 FINCH_PATH_AUTO = 0
 FINCH_PATH_SEPARATE = 1
 FINCH_PATH_FUSED = 2
+FINCH_PATH_OWNER = 3
 
 
 class FinchError(RuntimeError):
@@ -98,6 +99,10 @@ def load_library() -> ctypes.CDLL:
     lib.finch_profile.restype = ctypes.c_int
     lib.finch_profile_read.argtypes = [vp, P(ctypes.c_float), P(i32)]
     lib.finch_profile_read.restype = ctypes.c_int
+    lib.finch_loop_workspace_size.argtypes = [vp, P(finch_problem), P(i32), i32, P(sz)]
+    lib.finch_loop_workspace_size.restype = ctypes.c_int
+    lib.finch_loop.argtypes = [vp, P(finch_problem), vp, P(i32), vp, i32, vp, sz, vp]
+    lib.finch_loop.restype = ctypes.c_int
     lib.finch_set_option.argtypes = [vp, i32, i64]
     lib.finch_set_option.restype = ctypes.c_int
     lib.finch_check.argtypes = [vp, vp, P(i32)]
@@ -184,6 +189,23 @@ def finch_set_option(ctx, option: int, value: int) -> None:
     _check(load_library().finch_set_option(ctx, option, value), "finch_set_option", ctx)
 
 
+def finch_loop_workspace_size(ctx, host_desc, host_step_first, n_steps: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load_library().finch_loop_workspace_size(ctx, host_desc, host_step_first, n_steps,
+                                                    ctypes.byref(out)),
+           "finch_loop_workspace_size", ctx)
+    return out.value
+
+
+def finch_loop(ctx, host_desc, dev_desc: int, host_step_first, dev_step_first: int, n_steps: int,
+               workspace: int, workspace_bytes: int, stream: int = 0) -> None:
+    _check(load_library().finch_loop(ctx, host_desc, ctypes.c_void_p(dev_desc), host_step_first,
+                                     ctypes.c_void_p(dev_step_first), n_steps,
+                                     ctypes.c_void_p(workspace), workspace_bytes,
+                                     ctypes.c_void_p(stream)),
+           "finch_loop", ctx)
+
+
 def finch_check(ctx, stream: int = 0) -> int:
     """Synchronise the stream and return (and clear) the device error word."""
     out = ctypes.c_int32(0)
@@ -229,6 +251,26 @@ class Batch:
         raw = bytes(self.host)[: n * ctypes.sizeof(finch_problem)]
         self.dev = torch.frombuffer(bytearray(raw if raw else b"\0" * 8), dtype=torch.uint8).to(device)
         self.dev_ptr = self.dev.data_ptr()
+
+
+class LoopBatch:
+    """The descriptor arrays of all steps of a chunk loop, step after step, with the
+    table of where each step starts, on the host and on the device (finch_loop).
+
+    `steps` is a sequence of per-step problem lists as `Batch` takes them; slot j of
+    every step must describe the same problem and later steps may only drop slots
+    from the end."""
+
+    def __init__(self, steps: Sequence[Sequence[Dict]], device="cuda"):
+        import torch
+        flat = [pb for st in steps for pb in st]
+        self.batch = Batch(flat, device=device)
+        self.n_steps = len(steps)
+        first = [0]
+        for st in steps:
+            first.append(first[-1] + len(st))
+        self.host_first = (ctypes.c_int32 * len(first))(*first)
+        self.dev_first = torch.tensor(first, dtype=torch.int32, device=device)
 
 
 class Finch:
@@ -287,3 +329,17 @@ class Finch:
 
     def step(self, batch: Batch, stream=None):
         self._run("finch_step", batch, stream)
+
+    def reserve_loop(self, lb: LoopBatch) -> int:
+        import torch
+        need = finch_loop_workspace_size(self.ctx, lb.batch.host, lb.host_first, lb.n_steps)
+        if self.ws is None or self.ws.numel() < need:
+            self.ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
+        return need
+
+    def loop(self, lb: LoopBatch, stream=None):
+        import torch
+        self.reserve_loop(lb)
+        s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
+        finch_loop(self.ctx, lb.batch.host, lb.batch.dev_ptr, lb.host_first, lb.dev_first.data_ptr(),
+                   lb.n_steps, self.ws.data_ptr(), self.ws.numel(), s)

@@ -43,6 +43,9 @@ struct Plan {
   int32_t n_max = 0, rows_max = 0, rpad_max = 0, r_max = 0, tiles_max = 0, row_chunk = 32;
   int32_t score_stride = 0;
   bool step_ok = false;   // the batch can run as one kernel per step
+  bool own_ok = false;    // the batch can run with one workgroup per problem
+  int32_t own_row_chunk = 32;
+  size_t own_lds = 0;
   size_t lds_bytes = 0;
   size_t off_stats = 0, off_lse = 0, off_scores = 0, total = 0;
 };
@@ -65,7 +68,13 @@ size_t score_lds(const finch_ctx* ctx, int row_chunk) {
   return static_cast<size_t>(row_chunk) * (d * 4 + 4 * sizeof(float2));
 }
 
-finch_status make_plan(const finch_ctx* ctx, const finch_problem* hd, int32_t n, Plan& pl) {
+// Sizes launches for the n descriptors of `hd`; the workspace is laid out for
+// n_alloc problems (n itself unless the descriptors are several steps of n_alloc
+// slots, which reuse their slot's part of the workspace).
+finch_status make_plan(const finch_ctx* ctx, const finch_problem* hd, int32_t n_desc, Plan& pl,
+                       int32_t n_alloc = -1) {
+  const int32_t n = n_desc;
+  if (n_alloc < 0) n_alloc = n_desc;
   const int G = ctx->cfg.group_size;
   int64_t n_max = 0, rows_max = 0, r_max = 0;
   for (int32_t i = 0; i < n; ++i) {
@@ -104,13 +113,21 @@ finch_status make_plan(const finch_ctx* ctx, const finch_problem* hd, int32_t n,
                pl.lds_bytes + finch::kStepStaticLds <= ctx->max_lds &&
                n <= finch::kSyncMaxProblems &&
                (2 * static_cast<int64_t>(pl.tiles_max) + 16) * n < (int64_t{1} << 31);
+  if (ctx->cfg.dtype == FINCH_BF16 && n_max > 0) {
+    int orc = pl.rpad_max < finch::kOwnerMaxRowChunk ? pl.rpad_max : finch::kOwnerMaxRowChunk;
+    while (orc > 32 && finch::owner_lds_bytes(ctx->cfg.head_dim, orc) > ctx->max_lds) orc -= 32;
+    pl.own_row_chunk = orc;
+    pl.own_lds = finch::owner_lds_bytes(ctx->cfg.head_dim, orc);
+    pl.own_ok = pl.own_lds <= ctx->max_lds;
+  }
   size_t off = 0;
   pl.off_stats = off;
-  off = align_up(off + static_cast<size_t>(n) * pl.tiles_max * pl.rpad_max * sizeof(float2), 256);
+  const size_t na = static_cast<size_t>(n_alloc);
+  off = align_up(off + na * pl.tiles_max * pl.rpad_max * sizeof(float2), 256);
   pl.off_lse = off;
-  off = align_up(off + static_cast<size_t>(n) * pl.rpad_max * sizeof(float), 256);
+  off = align_up(off + na * pl.rpad_max * sizeof(float), 256);
   pl.off_scores = off;
-  off = align_up(off + static_cast<size_t>(n) * pl.score_stride * sizeof(float), 256);
+  off = align_up(off + na * pl.score_stride * sizeof(float), 256);
   pl.total = off;
   return FINCH_OK;
 }
@@ -222,11 +239,36 @@ struct ProfScope {
   }
 };
 
+// One workgroup per problem pays when the problems fill the chip's CUs in whole
+// rounds (one 16-wave workgroup per CU at a time): AUTO takes that path when the
+// last round would be at least 85 % full.
+bool owner_wanted(const finch_ctx* ctx, const Plan& pl, int32_t n) {
+  if (!pl.own_ok || n <= 0) return false;
+  if (ctx->step_path == FINCH_PATH_OWNER) return true;
+  if (ctx->step_path != FINCH_PATH_AUTO) return false;
+  const int64_t cu = ctx->n_cu > 0 ? ctx->n_cu : 256;
+  const int64_t rounds = (n + cu - 1) / cu;
+  return static_cast<int64_t>(n) * 100 >= rounds * cu * 85;
+}
+
+finch_status run_owner(finch_ctx* ctx, LaunchParams p, const Plan& pl, int stages, hipStream_t s) {
+  p.row_chunk = pl.own_row_chunk;
+  p.lds_bytes = static_cast<uint32_t>(pl.own_lds);
+  hipError_t e;
+  {
+    ProfScope ps(ctx, FINCH_KERNEL_OWNER, s);
+    e = finch::launch_owner_bf16(ctx->cfg.head_dim, p, stages, s);
+  }
+  return e == hipSuccess ? FINCH_OK : hip_fail(ctx, e);
+}
+
 finch_status run_score(finch_ctx* ctx, const LaunchParams& p, const Plan& pl, hipStream_t s) {
   if (p.n_problems == 0 || pl.tiles_max == 0) return FINCH_OK;
   hipError_t e = hipSuccess;
   const int d = ctx->cfg.head_dim;
   const bool bf16 = ctx->cfg.dtype == FINCH_BF16;
+  if (owner_wanted(ctx, pl, p.n_problems)) return run_owner(ctx, p, pl, /*stages=*/0, s);
+  if (ctx->step_path == FINCH_PATH_OWNER) return FINCH_ERR_UNSUPPORTED;
   // AUTO = one kernel per stage: measured faster than the single kernel on MI355X
   if (ctx->step_path == FINCH_PATH_FUSED && pl.step_ok) {
     {
@@ -274,6 +316,25 @@ finch_status run_gather(finch_ctx* ctx, const LaunchParams& p, int r_max, hipStr
   return e == hipSuccess ? FINCH_OK : hip_fail(ctx, e);
 }
 
+// Checks the step table of finch_loop; *n_desc = descriptors in all steps, *n_slots =
+// problems of step 0.
+finch_status check_steps(const int32_t* first, int32_t n_steps, int32_t* n_desc, int32_t* n_slots) {
+  if (n_steps < 0 || (n_steps > 0 && !first)) return FINCH_ERR_INVALID_ARG;
+  *n_desc = 0;
+  *n_slots = 0;
+  if (n_steps == 0) return FINCH_OK;
+  if (first[0] != 0) return FINCH_ERR_INVALID_ARG;
+  int32_t prev = INT32_MAX;
+  for (int32_t s = 0; s < n_steps; ++s) {
+    const int64_t cnt = static_cast<int64_t>(first[s + 1]) - first[s];
+    if (cnt < 0 || cnt > prev) return FINCH_ERR_INVALID_ARG;
+    prev = static_cast<int32_t>(cnt);
+  }
+  *n_desc = first[n_steps];
+  *n_slots = first[1] - first[0];
+  return FINCH_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -317,6 +378,7 @@ finch_status finch_create(const finch_config* cfg, finch_ctx** out) {
   if (e == hipSuccess && cfg->dtype == FINCH_BF16) {
     // the one-kernel-per-step path also has a few bytes of static LDS
     e = finch::set_max_lds_step(ctx->max_lds - finch::kStepStaticLds);
+    if (e == hipSuccess) e = finch::set_max_lds_owner(ctx->max_lds);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->sync), finch::kSyncWords * sizeof(unsigned));
     if (e == hipSuccess) e = hipMemset(ctx->sync, 0, finch::kSyncWords * sizeof(unsigned));
   }
@@ -346,7 +408,8 @@ finch_status finch_set_option(finch_ctx* ctx, int32_t option, int64_t value) {
   if (!ctx) return FINCH_ERR_INVALID_ARG;
   switch (option) {
     case FINCH_OPT_STEP_PATH:
-      if (value != FINCH_PATH_AUTO && value != FINCH_PATH_SEPARATE && value != FINCH_PATH_FUSED)
+      if (value != FINCH_PATH_AUTO && value != FINCH_PATH_SEPARATE && value != FINCH_PATH_FUSED &&
+          value != FINCH_PATH_OWNER)
         return FINCH_ERR_INVALID_ARG;
       ctx->step_path = static_cast<int>(value);
       return FINCH_OK;
@@ -489,7 +552,8 @@ finch_status finch_step(finch_ctx* ctx, const finch_problem* host_desc,
   if (n == 0) return FINCH_OK;
   const LaunchParams p = make_params(ctx, dev_desc, n, pl, ws);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  // AUTO = one kernel per stage: measured faster than the single kernel on MI355X
+  if (pl.tiles_max > 0 && owner_wanted(ctx, pl, n)) return run_owner(ctx, p, pl, /*stages=*/1, s);
+  if (ctx->step_path == FINCH_PATH_OWNER && pl.tiles_max > 0) return FINCH_ERR_UNSUPPORTED;
   if (ctx->step_path == FINCH_PATH_FUSED && pl.step_ok) {
     hipError_t e;
     {
@@ -506,6 +570,55 @@ finch_status finch_step(finch_ctx* ctx, const finch_problem* host_desc,
   if (pl.r_max == 0) return FINCH_OK;
   if ((st = run_select(ctx, p, s)) != FINCH_OK) return st;
   return run_gather(ctx, p, pl.r_max, s);
+}
+
+finch_status finch_loop_workspace_size(const finch_ctx* ctx, const finch_problem* host_desc,
+                                       const int32_t* host_step_first, int32_t n_steps, size_t* bytes) {
+  if (!ctx || !bytes) return FINCH_ERR_INVALID_ARG;
+  int32_t n_desc, n_slots;
+  finch_status st = check_steps(host_step_first, n_steps, &n_desc, &n_slots);
+  if (st != FINCH_OK) return st;
+  if (n_desc > 0 && !host_desc) return FINCH_ERR_INVALID_ARG;
+  Plan pl;
+  if ((st = make_plan(ctx, host_desc, n_desc, pl, n_slots)) != FINCH_OK) return st;
+  *bytes = pl.total;
+  return FINCH_OK;
+}
+
+finch_status finch_loop(finch_ctx* ctx, const finch_problem* host_desc, const finch_problem* dev_desc,
+                        const int32_t* host_step_first, const int32_t* dev_step_first, int32_t n_steps,
+                        void* ws, size_t ws_bytes, void* stream) {
+  if (!ctx) return FINCH_ERR_INVALID_ARG;
+  int32_t n_desc, n_slots;
+  finch_status st = check_steps(host_step_first, n_steps, &n_desc, &n_slots);
+  if (st != FINCH_OK) return st;
+  if ((st = check_common(ctx, host_desc, dev_desc, n_desc)) != FINCH_OK) return st;
+  if (n_steps > 0 && (!dev_step_first || !aligned(dev_step_first, 4))) return FINCH_ERR_INVALID_ARG;
+  Plan pl;
+  if ((st = make_plan(ctx, host_desc, n_desc, pl, n_slots)) != FINCH_OK) return st;
+  if ((st = validate(ctx, host_desc, n_desc, kNeedQK | kNeedIdx | kNeedGather)) != FINCH_OK) return st;
+  if ((st = check_workspace(pl, ws, ws_bytes)) != FINCH_OK) return st;
+  if (n_desc == 0 || pl.tiles_max == 0) return FINCH_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (owner_wanted(ctx, pl, n_slots)) {
+    LaunchParams p = make_params(ctx, dev_desc, n_desc, pl, ws);
+    p.row_chunk = pl.own_row_chunk;
+    p.lds_bytes = static_cast<uint32_t>(pl.own_lds);
+    hipError_t e;
+    {
+      ProfScope ps(ctx, FINCH_KERNEL_OWNER, s);
+      e = finch::launch_owner_loop_bf16(ctx->cfg.head_dim, p, dev_step_first, n_steps, n_slots, s);
+    }
+    return e == hipSuccess ? FINCH_OK : hip_fail(ctx, e);
+  }
+  if (ctx->step_path == FINCH_PATH_OWNER) return FINCH_ERR_UNSUPPORTED;
+  // one finch_step per step; a step's plan never needs more workspace than the loop's
+  for (int32_t i = 0; i < n_steps; ++i) {
+    const int32_t f = host_step_first[i], cnt = host_step_first[i + 1] - f;
+    if ((st = finch_step(ctx, host_desc + f, dev_desc + f, cnt, ws, ws_bytes, stream)) != FINCH_OK)
+      return st;
+  }
+  return FINCH_OK;
 }
 
 finch_status finch_schedule(int64_t n_cont, int32_t m, int64_t k, int32_t* r_out, int32_t r_len) {

@@ -20,6 +20,8 @@ __host__ __device__ inline int stream_slices(int n_keys, int slice_keys) {
   const int s = (n_keys + slice_keys / 2) / slice_keys;
   return s < 1 ? 1 : s;
 }
+// One-workgroup-per-problem path: most prompt rows staged per pass over the keys.
+constexpr int kOwnerMaxRowChunk = 256;
 // Rows copied by one workgroup of the compaction kernel.
 constexpr int kGatherRows = 64;
 // One-kernel-per-step path: most prompt rows (padded to 32) it is compiled for, an
@@ -72,6 +74,11 @@ hipError_t launch_gather(const LaunchParams& p, int row_bytes, int r_max, hipStr
 hipError_t launch_step_bf16(int head_dim, const LaunchParams& p, size_t lds, int parts,
                             hipStream_t s);
 hipError_t set_max_lds_step(size_t bytes);
+size_t owner_lds_bytes(int head_dim, int row_chunk);
+hipError_t launch_owner_bf16(int head_dim, const LaunchParams& p, int stages, hipStream_t s);
+hipError_t launch_owner_loop_bf16(int head_dim, const LaunchParams& p, const int* step_first,
+                                  int n_steps, int n_slots, hipStream_t s);
+hipError_t set_max_lds_owner(size_t bytes);
 // Raise the dynamic-LDS limit of the scoring kernels of one dtype to `bytes`.
 hipError_t set_max_lds_bf16(size_t bytes);
 hipError_t set_max_lds_f32(size_t bytes);

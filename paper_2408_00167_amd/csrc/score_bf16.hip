@@ -253,21 +253,23 @@ __global__ __launch_bounds__(kThreads, 4) void colsum_bf16(LaunchParams prm) {
 
     // key blocks are handed out by the workgroup's counter (each key's sum is
     // computed by one wave, so the result does not depend on who takes which)
+    // The slice is walked from its end: pass 1 read it front to back, so its tail is
+    // what the memory-side cache is most likely to still hold.
     bf16x8 ka[D / 16], kb[D / 16];
-    int b = b0 + next_block(sh_next, lane);
-    if (b < b1) {
+    int b = b1 - 1 - next_block(sh_next, lane);
+    if (b >= b0) {
       load_k_block<D>(pb, N, b << 5, lane, ka);
       while (true) {
-        int bn = b0 + next_block(sh_next, lane);
-        if (bn < b1) load_k_block<D>(pb, N, bn << 5, lane, kb);
+        int bn = b1 - 1 - next_block(sh_next, lane);
+        if (bn >= b0) load_k_block<D>(pb, N, bn << 5, lane, kb);
         process(ka, b);
         b = bn;
-        if (b >= b1) break;
-        bn = b0 + next_block(sh_next, lane);
-        if (bn < b1) load_k_block<D>(pb, N, bn << 5, lane, ka);
+        if (b < b0) break;
+        bn = b1 - 1 - next_block(sh_next, lane);
+        if (bn >= b0) load_k_block<D>(pb, N, bn << 5, lane, ka);
         process(kb, b);
         b = bn;
-        if (b >= b1) break;
+        if (b < b0) break;
       }
     }
     __syncthreads();

@@ -107,14 +107,27 @@ __device__ __forceinline__ void stage_q(const void* q, int R, int row0, int rows
                                         int tid) {
   constexpr int kSegs = D / 8;
   constexpr int kStride = D * 2 + 16;
+  constexpr int kBatch = 4;  // loads in flight per thread
   const FINCH_GLOBAL u32x4* src = as_global<u32x4>(q);
   const int total = rows * kSegs;
-  for (int i = tid; i < total; i += NT) {
-    const int row = i / kSegs;
-    const int seg = i - row * kSegs;
-    u32x4 val = {0u, 0u, 0u, 0u};
-    if (row0 + row < R) val = src[static_cast<size_t>(row0 + row) * kSegs + seg];
-    *reinterpret_cast<u32x4*>(lds_q + row * kStride + seg * 16) = val;
+  for (int i0 = tid; i0 < total; i0 += NT * kBatch) {
+    u32x4 val[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int i = i0 + u * NT;
+      const int row = i / kSegs;
+      const int seg = i - row * kSegs;
+      const u32x4 zero = {0u, 0u, 0u, 0u};
+      val[u] = zero;
+      if (i < total && row0 + row < R) val[u] = src[static_cast<size_t>(row0 + row) * kSegs + seg];
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int i = i0 + u * NT;
+      const int row = i / kSegs;
+      const int seg = i - row * kSegs;
+      if (i < total) *reinterpret_cast<u32x4*>(lds_q + row * kStride + seg * 16) = val[u];
+    }
   }
 }
 

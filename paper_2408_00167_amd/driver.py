@@ -3,8 +3,8 @@
 `ChunkLoop` lays out, once, everything the sequence of prefill steps needs - the
 ping-pong cache buffers, the per-step descriptor arrays on host and device, the
 r schedule from `finch_schedule` - so that running the loop is nothing but one
-`finch_step` call per chunk on a stream, with no allocation, no host
-synchronisation and no device-to-host readback in between.
+`finch_loop` call (or one `finch_step` call per chunk) on a stream, with no
+allocation, no host synchronisation and no device-to-host readback in between.
 
 All arithmetic of the method happens inside the library; this file only computes
 addresses.
@@ -15,7 +15,7 @@ from typing import Dict, List, Optional, Sequence
 
 import torch
 
-from . import Batch, Finch, finch_schedule
+from . import Batch, Finch, LoopBatch, finch_schedule
 
 
 class ChunkLoop:
@@ -76,10 +76,15 @@ class ChunkLoop:
         self.batches: List[Batch] = []
         self.active: List[List[int]] = []
         self.step_shapes: List[List[tuple]] = []
+        # problems with more steps first, so that the problems present at a step are
+        # always the leading slots (what finch_loop asks for)
+        order = sorted(range(P), key=lambda p: -len(self.rs[p]))
+        all_descs = []
         for i in range(self.n_steps):
             descs, act, shapes = [], [], []
             h = i if history else 0
-            for p, pb in enumerate(self.problems):
+            for p in order:
+                pb = self.problems[p]
                 if i >= len(self.rs[p]):
                     continue
                 c = self.rs[p][i - 1] if i > 0 else 0
@@ -103,13 +108,20 @@ class ChunkLoop:
             self.batches.append(Batch(descs, device=dev))
             self.active.append(act)
             self.step_shapes.append(shapes)
+            all_descs.append(descs)
         for b in self.batches:
             fin.reserve(b)
+        self.loop_batch = LoopBatch(all_descs, device=dev)
+        fin.reserve_loop(self.loop_batch)
 
-    def run(self, stream: Optional[int] = None) -> None:
-        """Enqueue every step; returns without synchronising."""
-        for b in self.batches:
-            self.fin.step(b, stream)
+    def run(self, stream: Optional[int] = None, per_step: bool = False) -> None:
+        """Enqueue the whole loop - one finch_loop call, or with `per_step` one
+        finch_step call per chunk; returns without synchronising."""
+        if per_step:
+            for b in self.batches:
+                self.fin.step(b, stream)
+        else:
+            self.fin.loop(self.loop_batch, stream)
 
     def final_cache(self, p: int):
         """(K~, V~) views of problem p after the last of its steps."""

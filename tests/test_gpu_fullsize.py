@@ -20,9 +20,10 @@ def say(msg):
     print(msg, flush=True)
 
 
-def run_full(name, n_sample, seed):
+def run_full(name, n_sample, seed, path=F.FINCH_PATH_AUTO):
     w = W.get_workload(name)
     fin = F.Finch(F.FINCH_BF16 if w.dtype == "bf16" else F.FINCH_F32, w.head_dim, w.group)
+    fin.set_step_path(path)
     triples = list(W.problems_of(w))
     say(f"{name}: drawing {len(triples)} problems on the GPU")
     probs = [H.make_gpu_problem(w, b, l, g) for b, l, g in triples]
@@ -88,6 +89,13 @@ def test_c3_full_size():
 @pytest.mark.timeout(900)
 def test_c4_full_size():
     run_full("C4", 4, seed=4)
+
+
+@pytest.mark.timeout(900)
+def test_c4_full_size_one_kernel_per_stage():
+    """AUTO runs these batches with one workgroup per problem; the per-stage kernels
+    are checked at full size too."""
+    run_full("C4", 2, seed=14, path=F.FINCH_PATH_SEPARATE)
 
 
 @pytest.mark.timeout(1200)

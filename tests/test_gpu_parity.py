@@ -59,14 +59,19 @@ def _which_scoring_kernels(fin, batch):
     return {k for k, v in prof.items() if v["launches"]}
 
 
+PATHS = {"fused": F.FINCH_PATH_FUSED, "separate": F.FINCH_PATH_SEPARATE, "owner": F.FINCH_PATH_OWNER}
+
+
 @pytest.mark.parametrize("d,group,path", [(128, 4, "fused"), (128, 4, "separate"), (64, 2, "fused"),
-                                          (128, 1, "fused"), (64, 8, "separate")])
+                                          (128, 1, "fused"), (64, 8, "separate"), (128, 4, "owner"),
+                                          (64, 2, "owner"), (128, 1, "owner"), (64, 8, "owner")])
 def test_both_step_paths(d, group, path):
     """One kernel per step (work items handing results to each other through device
-    memory) and one kernel per stage, each forced, on the same ragged batch."""
+    memory), one kernel per stage, and one workgroup per problem, each forced, on the
+    same ragged batch."""
     say(f"both_step_paths d={d} G={group} {path}")
     fin = F.Finch(F.FINCH_BF16, d, group)
-    fin.set_step_path(F.FINCH_PATH_FUSED if path == "fused" else F.FINCH_PATH_SEPARATE)
+    fin.set_step_path(PATHS[path])
     cap = 448 // group
     specs = [dict(s, n_que=min(s["n_que"], cap)) for s in RAGGED_SPECS]
     specs += [dict(n_que=cap, c=1364, m=4096, r=1408), dict(n_que=max(1, cap // 3), c=5, m=130, r=64)]
@@ -76,7 +81,8 @@ def test_both_step_paths(d, group, path):
     say(f"  worst score rel err {st['worst_rel']:.2e}, near-tie swaps {st['swaps']}")
     assert fin.check() == 0
     ran = _which_scoring_kernels(fin, batch)
-    assert ran == ({"step"} if path == "fused" else {"rowstats", "colsum", "select", "gather"}), ran
+    assert ran == {"fused": {"step"}, "owner": {"owner"},
+                   "separate": {"rowstats", "colsum", "select", "gather"}}[path], ran
     # a second launch on the same context: the synchronisation words were left clean
     for t in ts:
         t["scores"].fill_(-5.0)
@@ -151,10 +157,13 @@ def test_step_with_scores_in_workspace():
     fin.close()
 
 
-def test_many_prompt_rows_are_chunked():
-    """R = 4 * 160 = 640 > 512 staged rows: two passes over the prompt rows."""
-    say("many_prompt_rows")
+@pytest.mark.parametrize("path", ["separate", "owner"])
+def test_many_prompt_rows_are_chunked(path):
+    """R = 4 * 160 = 640 rows: more than are staged at a time (512 with one kernel per
+    stage, 256 with one workgroup per problem), so the keys are passed several times."""
+    say(f"many_prompt_rows {path}")
     fin = F.Finch(F.FINCH_BF16, 128, 4)
+    fin.set_step_path(PATHS[path])
     specs = [dict(n_que=160, c=100, m=500, r=77), dict(n_que=130, c=0, m=300, r=20)]
     batch, ts = H.single_step_case(fin, specs, torch.bfloat16, 128, 4, seed=9)
     fin.step(batch)
@@ -196,13 +205,15 @@ def test_large_logits_do_not_overflow():
     fin.close()
 
 
+@pytest.mark.parametrize("path", ["separate", "owner"])
 @pytest.mark.parametrize("kramp", [60.0, 1.0 / 60.0])
-def test_logits_far_from_the_first_blocks_reference(kramp):
+def test_logits_far_from_the_first_blocks_reference(kramp, path):
     """Key magnitudes rise (or fall) 60-fold along one slice, so the logits of later key
     blocks lie hundreds of powers of two above (below) those of the blocks a wave
     starts with: the reference of the running sums has to move (must not be needed)."""
-    say(f"logit ramp x{kramp:.3g}")
+    say(f"logit ramp x{kramp:.3g} {path}")
     fin = F.Finch(F.FINCH_BF16, 128, 4)
+    fin.set_step_path(PATHS[path])
     specs = [dict(n_que=12, c=0, m=3000, r=100, qscale=4.0, kramp=kramp),
              dict(n_que=40, c=10, m=2200, r=64, qscale=3.0, kramp=kramp)]
     batch, ts = H.single_step_case(fin, specs, torch.bfloat16, 128, 4, seed=12)
@@ -361,6 +372,62 @@ def test_per_step_queries_and_resume():
         torch.cuda.synchronize()
         Kc, Vc = t["k_out"], t["v_out"]
     assert torch.equal(Kc, Kt) and torch.equal(Vc, Vt)
+    fin.close()
+
+
+@pytest.mark.parametrize("path", ["owner", "separate"])
+def test_whole_loop_call_equals_step_by_step(path):
+    """finch_loop (one launch for all steps with one workgroup per slot, or its
+    step-by-step form) against one finch_step per chunk: problems of different
+    lengths (slots drop out from the end), a different Q per step for some, and the
+    oracle on every step of every problem."""
+    say(f"whole loop vs step by step ({path})")
+    w = W.get_workload("C4")
+    fin = F.Finch(F.FINCH_BF16, 128, 4)
+    fin.set_step_path(PATHS[path])
+    gen = torch.Generator(device="cuda"); gen.manual_seed(21)
+    lengths = [1500, 4096, 2600, 520, 3333, 4096]
+    probs = []
+    for j, n in enumerate(lengths):
+        pb = H.make_gpu_problem(w, 0, 0, j, n_cont=n)
+        pb["budget"] = max(8, n // 7)
+        if j % 2:
+            steps = (n + 511) // 512
+            pb["Q"] = [H.rand_storage(tuple(pb["Q"].shape), torch.bfloat16, gen) for _ in range(steps)]
+        probs.append(pb)
+    loops = []
+    for per_step in (False, True):
+        loop = ChunkLoop(fin, probs, 512, history=True)
+        loop.run(per_step=per_step)
+        st = H.validate_chunk_loop(loop, list(range(len(probs))), f"loop per_step={per_step}")
+        say(f"  per_step={per_step}: {st}")
+        loops.append(loop)
+    a, b = loops
+    assert torch.equal(a.scores, b.scores) and torch.equal(a.idx, b.idx)
+    for p in range(len(probs)):
+        for x, y in zip(a.final_cache(p), b.final_cache(p)):
+            assert torch.equal(x, y)
+    assert fin.check() == 0
+    fin.close()
+
+
+def test_loop_step_table_is_checked():
+    fin = F.Finch(F.FINCH_BF16, 128, 4)
+    batch, ts = H.single_step_case(fin, [dict(n_que=4, c=0, m=64, r=8)] * 3, torch.bfloat16, 128, 4, seed=3)
+    fin.reserve(batch)
+    dev_first = torch.tensor([0, 2, 3], dtype=torch.int32, device="cuda")
+
+    def call(first):
+        arr = (ctypes.c_int32 * len(first))(*first)
+        F.finch_loop(fin.ctx, batch.host, batch.dev_ptr, arr, dev_first.data_ptr(), len(first) - 1,
+                     fin.ws.data_ptr(), fin.ws.numel(), 0)
+
+    for bad in ([0, 1, 3], [1, 2, 3], [0, 2, 1]):   # growing step, not starting at 0, negative count
+        with pytest.raises(F.FinchError) as e:
+            call(bad)
+        assert e.value.status == F.FINCH_ERR_INVALID_ARG
+    call([0, 2, 3])
+    torch.cuda.synchronize()
     fin.close()
 
 
