@@ -173,7 +173,7 @@ def main() -> int:
         klass = {"rowstats": "score_pass", "colsum": "score_pass", "step": "step", "owner": "step",
                  "select": "select", "gather": "gather", "lse": "select"}[dom]
         launches = kernels[dom]["launches_per_step"]
-        # the one-kernel-per-step launch moves everything the step has to move
+        # a launch that runs all stages moves everything the step has to move
         per_kernel_bytes["step"] = 2 * per_kernel_bytes["score_pass"] + per_kernel_bytes["gather"]
         bytes_per_launch = per_kernel_bytes[klass] / launches
         achieved = bytes_per_launch / (kernels[dom]["avg_us"] * 1e-6) / 1e9

@@ -147,34 +147,15 @@ finch_status finch_schedule(int64_t n_cont, int32_t m, int64_t k, int32_t* r_out
  * exchanged between workgroups; batches it cannot run fail with
  * FINCH_ERR_UNSUPPORTED.  AUTO (default) takes OWNER when the batch has enough
  * problems to fill the chip's compute units in whole rounds, else SEPARATE.
- * FUSED runs finch_step (and finch_score) as ONE kernel when the batch allows it
- * (bf16, G*n_que <= 448; other batches fail with FINCH_ERR_UNSUPPORTED): its
- * workgroups take pass-1, pass-2, top-r and copy work items from a queue and hand
- * results to each other through device memory, so there are no kernel boundaries
- * between the stages.
- * FINCH_OPT_SPIN_LIMIT bounds how often a work item of the FUSED kernel polls for
- * results of work items that were started before it, before it gives up, raises
- * the context's device error word and carries on, so a launch always terminates.
  * One context must not run on two streams at the same time. */
 typedef enum {
   FINCH_OPT_STEP_PATH = 1,
-  FINCH_OPT_SPIN_LIMIT = 2,
-  /* tuning: target number of keys one workgroup of the bf16 scoring kernels
-   * streams (default 2400); a problem is cut into round((c+m)/value) slices */
+  /* tuning: target number of keys one workgroup of the two-pass bf16 scoring
+   * kernels streams (default 2400); a problem is cut into round((c+m)/value) slices */
   FINCH_OPT_SLICE_KEYS = 3
 } finch_option;
-typedef enum {
-  FINCH_PATH_AUTO = 0,
-  FINCH_PATH_SEPARATE = 1,
-  FINCH_PATH_FUSED = 2,
-  FINCH_PATH_OWNER = 3
-} finch_path;
+typedef enum { FINCH_PATH_AUTO = 0, FINCH_PATH_SEPARATE = 1, FINCH_PATH_OWNER = 3 } finch_path;
 finch_status finch_set_option(finch_ctx* ctx, int32_t option, int64_t value);
-
-/* Synchronises `stream`, then reports the context's device error word in
- * *device_error (0 = none; bit 0 = a bounded wait was abandoned and the outputs of
- * that launch are invalid) and clears it.  The only call that blocks. */
-finch_status finch_check(finch_ctx* ctx, void* stream, int32_t* device_error);
 
 /* Measurement helpers (not part of the method).  finch_profile(ctx, 1) creates a
  * pool of HIP events (this call allocates; make it outside any timed loop) and
@@ -190,9 +171,8 @@ typedef enum {
   FINCH_KERNEL_COLSUM = 2,   /* scoring pass 2: per-key sums of the weights  */
   FINCH_KERNEL_SELECT = 3,   /* top-r                                        */
   FINCH_KERNEL_GATHER = 4,   /* compaction                                   */
-  FINCH_KERNEL_STEP = 5,     /* all stages in one kernel (replaces 0..4)     */
-  FINCH_KERNEL_OWNER = 6,    /* all stages, one workgroup per problem        */
-  FINCH_KERNEL_COUNT = 7
+  FINCH_KERNEL_OWNER = 5,    /* all stages, one workgroup per problem        */
+  FINCH_KERNEL_COUNT = 6
 } finch_kernel;
 finch_status finch_profile(finch_ctx* ctx, int32_t enable);
 finch_status finch_profile_read(finch_ctx* ctx, float* ms, int32_t* launches);

@@ -30,17 +30,15 @@ EXPORTED_SYMBOLS = (
     "finch_create", "finch_destroy", "finch_workspace_size", "finch_score", "finch_topk",
     "finch_compact", "finch_step", "finch_schedule", "finch_last_hip_error",
     "finch_status_string", "finch_version", "finch_profile", "finch_profile_read",
-    "finch_set_option", "finch_check", "finch_loop", "finch_loop_workspace_size",
+    "finch_set_option", "finch_loop", "finch_loop_workspace_size",
 )
 
-KERNEL_NAMES = ("rowstats", "lse", "colsum", "select", "gather", "step", "owner")
+KERNEL_NAMES = ("rowstats", "lse", "colsum", "select", "gather", "owner")
 
 FINCH_OPT_STEP_PATH = 1
-FINCH_OPT_SPIN_LIMIT = 2
 FINCH_OPT_SLICE_KEYS = 3
 FINCH_PATH_AUTO = 0
 FINCH_PATH_SEPARATE = 1
-FINCH_PATH_FUSED = 2
 FINCH_PATH_OWNER = 3
 
 
@@ -105,8 +103,6 @@ def load_library() -> ctypes.CDLL:
     lib.finch_loop.restype = ctypes.c_int
     lib.finch_set_option.argtypes = [vp, i32, i64]
     lib.finch_set_option.restype = ctypes.c_int
-    lib.finch_check.argtypes = [vp, vp, P(i32)]
-    lib.finch_check.restype = ctypes.c_int
     lib.finch_version.argtypes = []
     lib.finch_version.restype = i32
     _lib = lib
@@ -206,14 +202,6 @@ def finch_loop(ctx, host_desc, dev_desc: int, host_step_first, dev_step_first: i
            "finch_loop", ctx)
 
 
-def finch_check(ctx, stream: int = 0) -> int:
-    """Synchronise the stream and return (and clear) the device error word."""
-    out = ctypes.c_int32(0)
-    _check(load_library().finch_check(ctx, ctypes.c_void_p(stream), ctypes.byref(out)),
-           "finch_check", ctx)
-    return out.value
-
-
 def finch_version() -> int:
     return load_library().finch_version()
 
@@ -298,11 +286,6 @@ class Finch:
 
     def set_step_path(self, path: int) -> None:
         finch_set_option(self.ctx, FINCH_OPT_STEP_PATH, path)
-
-    def check(self, stream=None) -> int:
-        import torch
-        s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
-        return finch_check(self.ctx, s)
 
     def reserve(self, batch: Batch) -> int:
         import torch

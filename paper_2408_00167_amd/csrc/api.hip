@@ -20,11 +20,8 @@ struct finch_ctx {
   int prof_used;
   hipEvent_t* prof_ev;   // 2 * kProfPairs events, or nullptr
   int* prof_kind;        // kernel class of each pair
-  // one-kernel-per-step path
-  unsigned* sync;        // device, finch::kSyncWords words, zero between launches
   int n_cu;              // compute units of the device
-  int step_path;         // FINCH_PATH_AUTO / _SEPARATE / _FUSED
-  uint32_t spin_limit;
+  int step_path;         // FINCH_PATH_AUTO / _SEPARATE / _OWNER
   int slice_keys;        // target keys per workgroup slice of the bf16 scoring kernels
 };
 
@@ -42,7 +39,6 @@ enum Need : unsigned {
 struct Plan {
   int32_t n_max = 0, rows_max = 0, rpad_max = 0, r_max = 0, tiles_max = 0, row_chunk = 32;
   int32_t score_stride = 0;
-  bool step_ok = false;   // the batch can run as one kernel per step
   bool own_ok = false;    // the batch can run with one workgroup per problem
   int32_t own_row_chunk = 32;
   size_t own_lds = 0;
@@ -108,11 +104,6 @@ finch_status make_plan(const finch_ctx* ctx, const finch_problem* hd, int32_t n_
   if (pg * (pl.tiles_max > 0 ? pl.tiles_max : 1) >= (int64_t{1} << 31)) return FINCH_ERR_CAPACITY;
   const int64_t gb = (static_cast<int64_t>(pl.r_max) + finch::kGatherRows - 1) / finch::kGatherRows;
   if (gb * n >= (int64_t{1} << 31)) return FINCH_ERR_CAPACITY;
-  pl.step_ok = ctx->cfg.dtype == FINCH_BF16 && ctx->sync && n_max > 0 &&
-               pl.rpad_max <= finch::kStepMaxRows && pl.row_chunk == pl.rpad_max &&
-               pl.lds_bytes + finch::kStepStaticLds <= ctx->max_lds &&
-               n <= finch::kSyncMaxProblems &&
-               (2 * static_cast<int64_t>(pl.tiles_max) + 16) * n < (int64_t{1} << 31);
   if (ctx->cfg.dtype == FINCH_BF16 && n_max > 0) {
     int orc = pl.rpad_max < finch::kOwnerMaxRowChunk ? pl.rpad_max : finch::kOwnerMaxRowChunk;
     while (orc > 32 && finch::owner_lds_bytes(ctx->cfg.head_dim, orc) > ctx->max_lds) orc -= 32;
@@ -209,8 +200,6 @@ LaunchParams make_params(const finch_ctx* ctx, const finch_problem* dd, int32_t 
   p.lse = reinterpret_cast<float*>(base + pl.off_lse);
   p.ws_scores = reinterpret_cast<float*>(base + pl.off_scores);
   p.lds_bytes = static_cast<uint32_t>(pl.lds_bytes);
-  p.spin_limit = ctx->spin_limit;
-  p.sync = ctx->sync;
   return p;
 }
 
@@ -269,15 +258,6 @@ finch_status run_score(finch_ctx* ctx, const LaunchParams& p, const Plan& pl, hi
   const bool bf16 = ctx->cfg.dtype == FINCH_BF16;
   if (owner_wanted(ctx, pl, p.n_problems)) return run_owner(ctx, p, pl, /*stages=*/0, s);
   if (ctx->step_path == FINCH_PATH_OWNER) return FINCH_ERR_UNSUPPORTED;
-  // AUTO = one kernel per stage: measured faster than the single kernel on MI355X
-  if (ctx->step_path == FINCH_PATH_FUSED && pl.step_ok) {
-    {
-      ProfScope ps(ctx, FINCH_KERNEL_STEP, s);
-      e = finch::launch_step_bf16(d, p, pl.lds_bytes, /*parts=*/0, s);
-    }
-    return e == hipSuccess ? FINCH_OK : hip_fail(ctx, e);
-  }
-  if (ctx->step_path == FINCH_PATH_FUSED) return FINCH_ERR_UNSUPPORTED;
   {
     ProfScope ps(ctx, FINCH_KERNEL_ROWSTATS, s);
     e = bf16 ? finch::launch_rowstats_bf16(d, p, pl.lds_bytes, s)
@@ -357,10 +337,8 @@ finch_status finch_create(const finch_config* cfg, finch_ctx** out) {
   ctx->prof_used = 0;
   ctx->prof_ev = nullptr;
   ctx->prof_kind = nullptr;
-  ctx->sync = nullptr;
   ctx->n_cu = 0;
   ctx->step_path = FINCH_PATH_AUTO;
-  ctx->spin_limit = 200000;
   ctx->slice_keys = finch::kDefaultSliceKeys;
   hipError_t e = hipGetDevice(&ctx->device);
   if (e == hipSuccess) {
@@ -375,19 +353,12 @@ finch_status finch_create(const finch_config* cfg, finch_ctx** out) {
     e = cfg->dtype == FINCH_BF16 ? finch::set_max_lds_bf16(ctx->max_lds)
                                  : finch::set_max_lds_f32(ctx->max_lds);
   }
-  if (e == hipSuccess && cfg->dtype == FINCH_BF16) {
-    // the one-kernel-per-step path also has a few bytes of static LDS
-    e = finch::set_max_lds_step(ctx->max_lds - finch::kStepStaticLds);
-    if (e == hipSuccess) e = finch::set_max_lds_owner(ctx->max_lds);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->sync), finch::kSyncWords * sizeof(unsigned));
-    if (e == hipSuccess) e = hipMemset(ctx->sync, 0, finch::kSyncWords * sizeof(unsigned));
-  }
+  if (e == hipSuccess && cfg->dtype == FINCH_BF16) e = finch::set_max_lds_owner(ctx->max_lds);
   if (e != hipSuccess) {
     // No usable GPU: there is no fallback path.  Report and hand nothing out.
     std::fprintf(stderr, "finch_create: HIP error %d (%s)\n", static_cast<int>(e),
                  hipGetErrorString(e));
     (void)hipGetLastError();
-    if (ctx->sync) (void)hipFree(ctx->sync);
     delete ctx;
     return FINCH_ERR_HIP;
   }
@@ -396,10 +367,7 @@ finch_status finch_create(const finch_config* cfg, finch_ctx** out) {
 }
 
 finch_status finch_destroy(finch_ctx* ctx) {
-  if (ctx) {
-    (void)finch_profile(ctx, 0);
-    if (ctx->sync) (void)hipFree(ctx->sync);
-  }
+  if (ctx) (void)finch_profile(ctx, 0);
   delete ctx;
   return FINCH_OK;
 }
@@ -408,14 +376,9 @@ finch_status finch_set_option(finch_ctx* ctx, int32_t option, int64_t value) {
   if (!ctx) return FINCH_ERR_INVALID_ARG;
   switch (option) {
     case FINCH_OPT_STEP_PATH:
-      if (value != FINCH_PATH_AUTO && value != FINCH_PATH_SEPARATE && value != FINCH_PATH_FUSED &&
-          value != FINCH_PATH_OWNER)
+      if (value != FINCH_PATH_AUTO && value != FINCH_PATH_SEPARATE && value != FINCH_PATH_OWNER)
         return FINCH_ERR_INVALID_ARG;
       ctx->step_path = static_cast<int>(value);
-      return FINCH_OK;
-    case FINCH_OPT_SPIN_LIMIT:
-      if (value < 1 || value > 0x7fffffff) return FINCH_ERR_INVALID_ARG;
-      ctx->spin_limit = static_cast<uint32_t>(value);
       return FINCH_OK;
     case FINCH_OPT_SLICE_KEYS:
       if (value < 256 || value > (1 << 24)) return FINCH_ERR_INVALID_ARG;
@@ -424,24 +387,6 @@ finch_status finch_set_option(finch_ctx* ctx, int32_t option, int64_t value) {
     default:
       return FINCH_ERR_INVALID_ARG;
   }
-}
-
-finch_status finch_check(finch_ctx* ctx, void* stream, int32_t* device_error) {
-  if (!ctx || !device_error) return FINCH_ERR_INVALID_ARG;
-  *device_error = 0;
-  hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
-  if (e != hipSuccess) return hip_fail(ctx, e);
-  if (!ctx->sync) return FINCH_OK;
-  unsigned word = 0;
-  e = hipMemcpy(&word, ctx->sync + finch::kSyncError, sizeof(word), hipMemcpyDeviceToHost);
-  if (e != hipSuccess) return hip_fail(ctx, e);
-  *device_error = static_cast<int32_t>(word);
-  if (word != 0) {
-    // a wait was abandoned: counters may be stale, so clear all of them
-    e = hipMemset(ctx->sync, 0, finch::kSyncWords * sizeof(unsigned));
-    if (e != hipSuccess) return hip_fail(ctx, e);
-  }
-  return FINCH_OK;
 }
 
 finch_status finch_profile(finch_ctx* ctx, int32_t enable) {
@@ -554,18 +499,6 @@ finch_status finch_step(finch_ctx* ctx, const finch_problem* host_desc,
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (pl.tiles_max > 0 && owner_wanted(ctx, pl, n)) return run_owner(ctx, p, pl, /*stages=*/1, s);
   if (ctx->step_path == FINCH_PATH_OWNER && pl.tiles_max > 0) return FINCH_ERR_UNSUPPORTED;
-  if (ctx->step_path == FINCH_PATH_FUSED && pl.step_ok) {
-    hipError_t e;
-    {
-      ProfScope ps(ctx, FINCH_KERNEL_STEP, s);
-      // copy items per problem: about 512 kept rows each
-      int parts = (pl.r_max + 511) / 512;
-      parts = parts < 1 ? 1 : parts > 16 ? 16 : parts;
-      e = finch::launch_step_bf16(ctx->cfg.head_dim, p, pl.lds_bytes, parts, s);
-    }
-    return e == hipSuccess ? FINCH_OK : hip_fail(ctx, e);
-  }
-  if (ctx->step_path == FINCH_PATH_FUSED && pl.tiles_max > 0) return FINCH_ERR_UNSUPPORTED;
   if ((st = run_score(ctx, p, pl, s)) != FINCH_OK) return st;
   if (pl.r_max == 0) return FINCH_OK;
   if ((st = run_select(ctx, p, s)) != FINCH_OK) return st;

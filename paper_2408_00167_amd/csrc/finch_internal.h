@@ -24,17 +24,6 @@ __host__ __device__ inline int stream_slices(int n_keys, int slice_keys) {
 constexpr int kOwnerMaxRowChunk = 256;
 // Rows copied by one workgroup of the compaction kernel.
 constexpr int kGatherRows = 64;
-// One-kernel-per-step path: most prompt rows (padded to 32) it is compiled for, an
-// upper bound of its static LDS, and the layout of the context-owned
-// synchronisation words (all uint32, all zero between launches).
-constexpr int kStepMaxRows = 448;
-constexpr int kStepStaticLds = 256;
-constexpr int kSyncTicket = 0;      // next work item of the current launch
-constexpr int kSyncDone = 128;      // workgroups of the current launch that retired
-constexpr int kSyncError = 129;     // sticky error bits (bit 0: a wait ran past its limit)
-constexpr int kSyncProblems = 256;  // then per problem: {pass-1 arrivals, pass-2 arrivals}
-constexpr int kSyncMaxProblems = 32768;
-constexpr int kSyncWords = kSyncProblems + 2 * kSyncMaxProblems;
 
 // Everything the scoring / selection / compaction kernels need besides the
 // descriptors.  Passed by value.
@@ -55,11 +44,7 @@ struct LaunchParams {
   float2* stats;               // [P][tiles_max][rpad_max] partial (max, sum) per tile
   float* lse;                  // [P][rpad_max] log2-domain log-sum-exp per prompt row
   float* ws_scores;            // [P][score_stride] used when desc.scores == NULL
-  // one-kernel-per-step path only
   uint32_t lds_bytes;          // dynamic LDS of the launch
-  uint32_t spin_limit;         // polls after which a waiting workgroup gives up
-  unsigned* sync;              // kSyncWords words owned by the context, all zero
-                               // between launches
 };
 
 // Launchers; each returns hipGetLastError() after the launch.
@@ -71,9 +56,6 @@ hipError_t launch_colsum_f32(int head_dim, const LaunchParams& p, size_t lds, hi
 hipError_t launch_lse(const LaunchParams& p, hipStream_t s);
 hipError_t launch_select(const LaunchParams& p, hipStream_t s);
 hipError_t launch_gather(const LaunchParams& p, int row_bytes, int r_max, hipStream_t s);
-hipError_t launch_step_bf16(int head_dim, const LaunchParams& p, size_t lds, int parts,
-                            hipStream_t s);
-hipError_t set_max_lds_step(size_t bytes);
 size_t owner_lds_bytes(int head_dim, int row_chunk);
 hipError_t launch_owner_bf16(int head_dim, const LaunchParams& p, int stages, hipStream_t s);
 hipError_t launch_owner_loop_bf16(int head_dim, const LaunchParams& p, const int* step_first,

@@ -1,4 +1,5 @@
-// Device helpers shared by the bf16 scoring kernels (two-pass and fused).
+// Device helpers shared by the bf16 scoring kernels (one kernel per stage, and one
+// workgroup per problem).
 #pragma once
 
 #include "finch_internal.h"

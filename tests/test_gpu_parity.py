@@ -46,7 +46,6 @@ def test_step_ragged_batch(dtype, d, group):
     fin.step(batch)
     st = H.validate_single_step(ts, f"step {dtype} d={d}")
     say(f"  worst score rel err {st['worst_rel']:.2e}, near-tie swaps {st['swaps']}")
-    assert fin.check() == 0
     fin.close()
 
 
@@ -59,72 +58,44 @@ def _which_scoring_kernels(fin, batch):
     return {k for k, v in prof.items() if v["launches"]}
 
 
-PATHS = {"fused": F.FINCH_PATH_FUSED, "separate": F.FINCH_PATH_SEPARATE, "owner": F.FINCH_PATH_OWNER}
+PATHS = {"separate": F.FINCH_PATH_SEPARATE, "owner": F.FINCH_PATH_OWNER}
 
 
-@pytest.mark.parametrize("d,group,path", [(128, 4, "fused"), (128, 4, "separate"), (64, 2, "fused"),
-                                          (128, 1, "fused"), (64, 8, "separate"), (128, 4, "owner"),
+@pytest.mark.parametrize("d,group,path", [(128, 4, "separate"), (64, 8, "separate"), (128, 4, "owner"),
                                           (64, 2, "owner"), (128, 1, "owner"), (64, 8, "owner")])
 def test_both_step_paths(d, group, path):
-    """One kernel per step (work items handing results to each other through device
-    memory), one kernel per stage, and one workgroup per problem, each forced, on the
-    same ragged batch."""
+    """One kernel per stage and one workgroup per problem, each forced, on the same
+    ragged batch."""
     say(f"both_step_paths d={d} G={group} {path}")
     fin = F.Finch(F.FINCH_BF16, d, group)
     fin.set_step_path(PATHS[path])
-    cap = 448 // group
+    cap = 512 // group
     specs = [dict(s, n_que=min(s["n_que"], cap)) for s in RAGGED_SPECS]
     specs += [dict(n_que=cap, c=1364, m=4096, r=1408), dict(n_que=max(1, cap // 3), c=5, m=130, r=64)]
     batch, ts = H.single_step_case(fin, specs, torch.bfloat16, d, group, seed=300 + d + group)
     fin.step(batch)
     st = H.validate_single_step(ts, f"{path} d={d} G={group}")
     say(f"  worst score rel err {st['worst_rel']:.2e}, near-tie swaps {st['swaps']}")
-    assert fin.check() == 0
     ran = _which_scoring_kernels(fin, batch)
-    assert ran == {"fused": {"step"}, "owner": {"owner"},
-                   "separate": {"rowstats", "colsum", "select", "gather"}}[path], ran
-    # a second launch on the same context: the synchronisation words were left clean
+    assert ran == {"owner": {"owner"}, "separate": {"rowstats", "colsum", "select", "gather"}}[path], ran
+    # a second launch on the same context
     for t in ts:
         t["scores"].fill_(-5.0)
     fin.step(batch)
     H.validate_single_step(ts, f"{path} again")
-    assert fin.check() == 0
     fin.close()
 
 
-def test_forced_fused_rejects_unsupported_batches():
-    fin = F.Finch(F.FINCH_BF16, 128, 4)
-    fin.set_step_path(F.FINCH_PATH_FUSED)
-    batch, ts = H.single_step_case(fin, [dict(n_que=128, c=10, m=100, r=5)], torch.bfloat16, 128, 4, 1)
+def test_forced_owner_path_rejects_fp32():
+    fin = F.Finch(F.FINCH_F32, 64, 1)
+    fin.set_step_path(F.FINCH_PATH_OWNER)
+    batch, ts = H.single_step_case(fin, [dict(n_que=4, c=0, m=64, r=8)], torch.float32, 64, 1, seed=1)
     with pytest.raises(F.FinchError) as e:
         fin.step(batch)
     assert e.value.status == F.FINCH_ERR_UNSUPPORTED
     fin.set_step_path(F.FINCH_PATH_AUTO)
-    fin.step(batch)                       # falls back to one kernel per stage
-    H.validate_single_step(ts, "auto fallback")
-    fin.close()
-
-
-def test_abandoned_wait_is_reported_and_recoverable():
-    """A spin limit of one poll, set from the host, makes waiting workgroups give up:
-    the launch still terminates, finch_check reports it, and the next launch with
-    the normal limit is correct again."""
-    say("abandoned wait")
-    fin = F.Finch(F.FINCH_BF16, 128, 4)
-    fin.set_step_path(F.FINCH_PATH_FUSED)
-    specs = [dict(n_que=48, c=1364, m=4096, r=1408)] * 24
-    batch, ts = H.single_step_case(fin, specs, torch.bfloat16, 128, 4, seed=12)
-    F.finch_set_option(fin.ctx, F.FINCH_OPT_SPIN_LIMIT, 1)
     fin.step(batch)
-    err = fin.check()
-    say(f"  device error word with spin limit 1: {err}")
-    assert err in (0, 1)
-    F.finch_set_option(fin.ctx, F.FINCH_OPT_SPIN_LIMIT, 200000)
-    for t in ts:
-        t["scores"].fill_(-5.0)
-    fin.step(batch)
-    H.validate_single_step(ts[:3], "after an abandoned wait")
-    assert fin.check() == 0
+    H.validate_single_step(ts, "fp32 after the rejected call")
     fin.close()
 
 
@@ -407,7 +378,6 @@ def test_whole_loop_call_equals_step_by_step(path):
     for p in range(len(probs)):
         for x, y in zip(a.final_cache(p), b.final_cache(p)):
             assert torch.equal(x, y)
-    assert fin.check() == 0
     fin.close()
 
 
