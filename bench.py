@@ -29,10 +29,11 @@ COPY_CALIBRATION_BYTES = 1 << 30
 # reads for the 1 GiB elementwise copy of --copy-calibration).  Offline figures:
 # bench.py cannot read counters itself.  None = not measured for that kernel/workload.
 MEASURED_TRAFFIC = {"C4": {
-    "rowstats": 2.0 * 159449.5 * 1024 + 768.0 * 1024,
-    "colsum": 2.0 * 159521.3 * 1024 + 4780.0 * 1024,
-    "select": 2.0 * 2464.5 * 1024 + 728.0 * 1024,
-    "gather": 2.0 * 47121.8 * 1024 + 92928.0 * 1024,
+    "rowstats": 2.0 * 159794.9 * 1024 + 1792.0 * 1024,
+    "colsum": 2.0 * 159570.6 * 1024 + 5804.0 * 1024,
+    "select": 2.0 * 2520.6 * 1024 + 728.0 * 1024,
+    "gather": 2.0 * 47121.4 * 1024 + 92928.0 * 1024,
+    "owner": 2.0 * 12845285.2 * 1024 + 4118656.1 * 1024,   # one launch = the whole loop
 }}
 
 
@@ -87,6 +88,10 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C4")
+    ap.add_argument("--path", default="auto", choices=["auto", "separate", "owner"],
+                    help="launch path of the library (auto: its own choice)")
+    ap.add_argument("--per-step", action="store_true",
+                    help="one finch_step call per chunk instead of one finch_loop call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -114,6 +119,8 @@ def main() -> int:
     dev = "cuda:0"
     w = W.get_workload(args.workload)
     fin = F.Finch(F.FINCH_BF16 if w.dtype == "bf16" else F.FINCH_F32, w.head_dim, w.group, device=dev)
+    fin.set_step_path({"auto": F.FINCH_PATH_AUTO, "separate": F.FINCH_PATH_SEPARATE,
+                       "owner": F.FINCH_PATH_OWNER}[args.path])
 
     t_gen = time.perf_counter()
     probs = []
@@ -128,13 +135,13 @@ def main() -> int:
     n_tokens = sum(r.n_cont for r in w.requests)
 
     for _ in range(args.warmup):
-        loop.run()
+        loop.run(per_step=args.per_step)
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     ev0.record()
     for _ in range(args.steps):
-        loop.run()
+        loop.run(per_step=args.per_step)
     ev1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
@@ -159,7 +166,7 @@ def main() -> int:
         torch.cuda.synchronize()
         tp = time.perf_counter()
         for _ in range(prof_steps):
-            loop.run()
+            loop.run(per_step=args.per_step)
         torch.cuda.synchronize()
         prof_ms = (time.perf_counter() - tp) * 1e3 / prof_steps
         prof = F.finch_profile_read(fin.ctx)
@@ -170,11 +177,11 @@ def main() -> int:
                 kernels[name] = dict(avg_us=1e3 * v["ms"] / v["launches"], launches_per_step=v["launches"] // prof_steps,
                                      ms_per_step=v["ms"] / prof_steps)
         dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
-        klass = {"rowstats": "score_pass", "colsum": "score_pass", "step": "step", "owner": "step",
+        klass = {"rowstats": "score_pass", "colsum": "score_pass", "owner": "step",
                  "select": "select", "gather": "gather", "lse": "select"}[dom]
         launches = kernels[dom]["launches_per_step"]
-        # a launch that runs all stages moves everything the step has to move
-        per_kernel_bytes["step"] = 2 * per_kernel_bytes["score_pass"] + per_kernel_bytes["gather"]
+        # a launch that runs all stages: everything the method has to move (keys once)
+        per_kernel_bytes["step"] = total_bytes
         bytes_per_launch = per_kernel_bytes[klass] / launches
         achieved = bytes_per_launch / (kernels[dom]["avg_us"] * 1e-6) / 1e9
         roofline = dict(bound="hbm", kernel=dom, achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s",
@@ -195,6 +202,7 @@ def main() -> int:
         "config": {"workload": f"{w.name}: {w.note}", "problems": w.n_problems,
                    "document_tokens": n_tokens, "chunk": w.chunk, "chunk_steps": loop.n_steps,
                    "head_dim": w.head_dim, "group": w.group,
+                   "path": args.path, "calls": "finch_step per chunk" if args.per_step else "finch_loop",
                    "prompt_rows": [w.rows(r) for r in w.requests][:4],
                    "budget": [r.budget for r in w.requests][:4], "keys_scored": keys},
         "path": {"algorithmic_bytes": total_bytes, "achieved_GBps": path_gbps,
