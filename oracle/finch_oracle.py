@@ -34,6 +34,21 @@ r >= N is the identity), the schedule's closed forms, single-chunk == one-shot,
 sigma = 1 == identity, and planted-mistake tests showing that a dropped scale, a
 transposed operand, a wrong axis, a wrong tie rule or a wrong concatenation order
 each break at least one pin.  `reposition` is pinned by the paper's worked example.
+
+Re-positioning of the kept keys (Managing the Cache: the positional embedding of a
+kept pair is adjusted to the slot it moves to; for rotary embeddings that is a
+rotation by the slot difference): `rope_rotate`, `kept_slots`,
+`compact_repositioned`.  Readings: a candidate's current position is its index in
+[cache ; chunk]; its new position is its slot in the new cache - slot t for the
+t-th kept index in ascending order, or, as in the paper's worked example, the
+rank of its score among the kept ones (highest first, ties to the lower index);
+the rotary pairing is either (u, u + d/2) ("half", the Llama layout the paper
+names) or (2u, 2u+1) ("interleaved", RoFormer's own); theta_u = base^(-2u/d).
+Pins: a rotation by zero is the identity bit for bit, rotations add up, pair norms
+are kept, dot products of two rotated vectors depend only on the difference of
+their positions, the closed form (1, 0) -> (cos a, sin a), numpy's complex
+multiplication as an independent statement of the same rotation, and the worked
+example's moves (-3, -4, +2) for the slots.
 """
 from __future__ import annotations
 
@@ -43,7 +58,8 @@ from typing import List, Optional, Sequence, Tuple
 import numpy as np
 
 __all__ = ["widen", "attention_weights", "key_scores", "top_r", "gather_rows",
-           "step", "schedule", "compress", "reposition"]
+           "step", "schedule", "compress", "reposition", "rope_frequencies", "rope_rotate",
+           "kept_slots", "compact_repositioned"]
 
 
 def widen(x: np.ndarray) -> np.ndarray:
@@ -165,3 +181,67 @@ def reposition(ranking: Sequence[int]) -> List[int]:
     ranking[t] goes to new slot t; negative = towards the start.
     """
     return [t - int(old) for t, old in enumerate(ranking)]
+
+
+def rope_frequencies(d: int, base: float) -> np.ndarray:
+    """theta_u = base^(-2u/d), u = 0 .. d/2 - 1: the rotary embedding's angle per
+    position step of channel pair u (RoFormer, as used by Llama 2, which the
+    paper's Managing the Cache names)."""
+    u = np.arange(d // 2, dtype=np.float64)
+    return np.power(float(base), -2.0 * u / float(d))
+
+
+def rope_rotate(K: np.ndarray, delta: np.ndarray, base: float, pairing: str) -> np.ndarray:
+    """Rows of K moved by delta[t] positions (Managing the Cache: the cosine and
+    sine needed for rotating to earlier or later positions): channel pair u of row
+    t is turned by the angle delta[t] * theta_u.  Returns float64; rows with
+    delta == 0 come back unchanged.
+    """
+    X = widen(K)
+    n, d = X.shape
+    ang = np.asarray(delta, dtype=np.float64)[:, None] * rope_frequencies(d, base)[None, :]
+    cs, sn = np.cos(ang), np.sin(ang)
+    if pairing == "half":
+        a, b = X[:, :d // 2], X[:, d // 2:]
+        out = np.concatenate([a * cs - b * sn, b * cs + a * sn], axis=1)
+    elif pairing == "interleaved":
+        a, b = X[:, 0::2], X[:, 1::2]
+        out = np.empty_like(X)
+        out[:, 0::2] = a * cs - b * sn
+        out[:, 1::2] = b * cs + a * sn
+    else:
+        raise ValueError(pairing)
+    return out
+
+
+def kept_slots(idx: np.ndarray, scores: np.ndarray, order: str) -> np.ndarray:
+    """New cache slot of each kept candidate idx[t] (idx ascending).  "ascending":
+    slot t.  "rank": the kept ones packed by relevance, highest score first, equal
+    scores by index (Managing the Cache, worked example)."""
+    idx = np.asarray(idx, dtype=np.int64)
+    if order == "ascending":
+        return np.arange(idx.shape[0], dtype=np.int64)
+    if order != "rank":
+        raise ValueError(order)
+    by_rank = np.argsort(-np.asarray(scores)[idx], kind="stable")   # kept entry at each slot
+    slots = np.empty(idx.shape[0], dtype=np.int64)
+    slots[by_rank] = np.arange(idx.shape[0], dtype=np.int64)
+    return slots
+
+
+def compact_repositioned(idx, scores, K_cache, K_chunk, V_cache, V_chunk, base: float,
+                         pairing: Optional[str], order: str):
+    """The new cache with re-positioned keys: candidate idx[t] goes to slot
+    kept_slots(...)[t]; its key is rotated by (slot - idx[t]) positions (not at all
+    if `pairing` is None), its value is copied.  Returns (K' float64, V' as
+    stored, slots)."""
+    idx = np.asarray(idx, dtype=np.int64)
+    slots = kept_slots(idx, scores, order)
+    Ksel = gather_rows(idx, K_cache, K_chunk)
+    Vsel = gather_rows(idx, V_cache, V_chunk)
+    Krot = widen(Ksel) if pairing is None else rope_rotate(Ksel, slots - idx, base, pairing)
+    Kout = np.empty_like(Krot)
+    Vout = np.empty_like(Vsel)
+    Kout[slots] = Krot
+    Vout[slots] = Vsel
+    return Kout, Vout, slots

@@ -361,4 +361,116 @@ def pin_reposition_example(O):
     assert O.reposition(ranking) == [r[1] for r in rows]
 
 
+def golden_lines(name):
+    with open(os.path.join(GOLDEN, name)) as f:
+        return [ln.strip() for ln in f if ln.strip() and not ln.startswith("#")]
+
+
+def pin_rope_zero_shift_is_identity(O):
+    rng = np.random.default_rng(31)
+    K = rng.standard_normal((5, 16)).astype(np.float32)
+    for pairing in ("half", "interleaved"):
+        out = O.rope_rotate(K, np.zeros(5), 10000.0, pairing)
+        assert out.tobytes() == K.astype(np.float64).tobytes()
+
+
+def pin_rope_closed_form(O):
+    # d = 2: one pair, theta_0 = 1, so a shift by a turns (1, 0) into (cos a, sin a)
+    # and (0, 1) into (-sin a, cos a), for any base and either pairing
+    for pairing in ("half", "interleaved"):
+        for a in (1.0, -2.5, 7.0):
+            out = O.rope_rotate(np.array([[1.0, 0.0], [0.0, 1.0]], dtype=np.float32), [a, a], 123.0, pairing)
+            want = np.array([[math.cos(a), math.sin(a)], [-math.sin(a), math.cos(a)]])
+            assert np.abs(out - want).max() < 1e-15
+    # theta_u = base^(-2u/d): with d = 4 and base 100 the second pair turns 10 times slower
+    f = O.rope_frequencies(4, 100.0)
+    assert abs(f[0] - 1.0) < 1e-15 and abs(f[1] - 0.1) < 1e-15
+    out = O.rope_rotate(np.array([[0.0, 1.0, 0.0, 0.0]], dtype=np.float32), [5.0], 100.0, "half")
+    # half pairing: channel 1 pairs with channel 3 and is pair u = 1
+    assert np.abs(out - np.array([[0.0, math.cos(0.5), 0.0, math.sin(0.5)]])).max() < 1e-15
+    out = O.rope_rotate(np.array([[0.0, 0.0, 1.0, 0.0]], dtype=np.float32), [5.0], 100.0, "interleaved")
+    # interleaved pairing: channel 2 pairs with channel 3 and is pair u = 1
+    assert np.abs(out - np.array([[0.0, 0.0, math.cos(0.5), math.sin(0.5)]])).max() < 1e-15
+
+
+def pin_rope_against_complex_multiplication(O):
+    rng = np.random.default_rng(32)
+    d, n, base = 32, 7, 500000.0
+    K = rng.standard_normal((n, d)).astype(np.float32)
+    delta = rng.integers(-3000, 3000, n)
+    theta = np.array([base ** (-2.0 * u / d) for u in range(d // 2)])
+    for pairing in ("half", "interleaved"):
+        out = O.rope_rotate(K, delta, base, pairing)
+        K64 = K.astype(np.float64)
+        a, b = (K64[:, :d // 2], K64[:, d // 2:]) if pairing == "half" else (K64[:, 0::2], K64[:, 1::2])
+        z = (a + 1j * b) * np.exp(1j * delta[:, None] * theta[None, :])
+        got = (out[:, :d // 2] + 1j * out[:, d // 2:]) if pairing == "half" else (out[:, 0::2] + 1j * out[:, 1::2])
+        assert np.abs(got - z).max() < 1e-12
+
+
+def pin_rope_shifts_add_and_keep_relative_positions(O):
+    rng = np.random.default_rng(33)
+    d, base = 64, 10000.0
+    q = rng.standard_normal((1, d)).astype(np.float32)
+    k = rng.standard_normal((1, d)).astype(np.float32)
+    for pairing in ("half", "interleaved"):
+        once = O.rope_rotate(k, [17 - 40], base, pairing)
+        twice = O.rope_rotate(O.rope_rotate(k, [-30], base, pairing), [7], base, pairing)
+        assert np.abs(once - twice).max() < 1e-12
+        # pair norms do not change
+        n0 = (k.astype(np.float64) ** 2).sum()
+        assert abs((once ** 2).sum() - n0) < 1e-10
+        # a key encoded at position 40 and moved to 17 meets a query at position 20 exactly
+        # as a key that was encoded at 17 in the first place: only differences count
+        k40 = O.rope_rotate(k, [40], base, pairing)
+        k17 = O.rope_rotate(k, [17], base, pairing)
+        q20 = O.rope_rotate(q, [20], base, pairing)
+        moved = O.rope_rotate(k40, [17 - 40], base, pairing)
+        assert np.abs(moved - k17).max() < 1e-12
+        assert abs((q20 * moved).sum() - (O.rope_rotate(q, [3], base, pairing) * k.astype(np.float64)).sum()) < 1e-10
+
+
+def pin_kept_slots_worked_example(O):
+    # Managing the Cache: cache [0..5], relevance ranking [3, 5, 0]
+    moves = {}
+    for line in golden_lines("reposition_example.txt"):
+        e, mv = line.split()
+        moves[int(e)] = int(mv)
+    scores = np.array([0.3, 0.0, 0.01, 0.9, 0.02, 0.5])
+    idx = O.top_r(scores, 3)
+    assert idx.tolist() == [0, 3, 5]
+    slots = O.kept_slots(idx, scores, "rank")
+    assert slots.tolist() == [2, 0, 1]
+    assert {int(i): int(s - i) for i, s in zip(idx, slots)} == moves
+    assert O.kept_slots(idx, scores, "ascending").tolist() == [0, 1, 2]
+    # equal scores keep their index order
+    assert O.kept_slots(np.array([1, 2, 4]), np.array([0, .5, .5, 0, .5]), "rank").tolist() == [0, 1, 2]
+
+
+def pin_compact_repositioned(O):
+    rng = np.random.default_rng(34)
+    d, c, m = 8, 4, 5
+    Kc, Kk = rng.standard_normal((c, d)).astype(np.float32), rng.standard_normal((m, d)).astype(np.float32)
+    Vc, Vk = rng.standard_normal((c, d)).astype(np.float32), rng.standard_normal((m, d)).astype(np.float32)
+    scores = rng.random(c + m)
+    idx = O.top_r(scores, 4)
+    allK, allV = np.concatenate([Kc, Kk]), np.concatenate([Vc, Vk])
+    # no rotation, ascending: the plain compaction
+    K0, V0, s0 = O.compact_repositioned(idx, scores, Kc, Kk, Vc, Vk, 1e4, None, "ascending")
+    assert K0.tobytes() == allK[idx].astype(np.float64).tobytes() and V0.tobytes() == allV[idx].tobytes()
+    # rank order: slot 0 holds the best candidate, values travel with their keys, and
+    # each key is turned by (slot - old index) positions, checked row by row
+    K1, V1, s1 = O.compact_repositioned(idx, scores, Kc, Kk, Vc, Vk, 1e4, "half", "rank")
+    best = int(idx[np.argmax(scores[idx])])
+    assert V1[0].tobytes() == allV[best].tobytes()
+    assert sorted(s1.tolist()) == list(range(4))
+    for t, j in enumerate(idx):
+        want = O.rope_rotate(allK[j:j + 1], [int(s1[t]) - int(j)], 1e4, "half")[0]
+        assert np.abs(K1[s1[t]] - want).max() < 1e-15
+        assert V1[s1[t]].tobytes() == allV[j].tobytes()
+    # ascending order never moves a key to a later position
+    K2, V2, s2 = O.compact_repositioned(idx, scores, Kc, Kk, Vc, Vk, 1e4, "interleaved", "ascending")
+    assert ((s2 - idx) <= 0).all()
+
+
 ALL_PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_") and callable(v)]

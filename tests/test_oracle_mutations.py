@@ -14,6 +14,22 @@ SRC = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
                    "oracle", "finch_oracle.py")
 
 MUTATIONS = {
+    "rope_sine_sign": ("out = np.concatenate([a * cs - b * sn, b * cs + a * sn], axis=1)",
+                       "out = np.concatenate([a * cs + b * sn, b * cs - a * sn], axis=1)"),
+    "rope_interleaved_sine_sign": ("out[:, 0::2] = a * cs - b * sn\n        out[:, 1::2] = b * cs + a * sn",
+                                   "out[:, 0::2] = a * cs + b * sn\n        out[:, 1::2] = b * cs - a * sn"),
+    "rope_pairings_swapped": ("if pairing == \"half\":\n        a, b = X[:, :d // 2], X[:, d // 2:]",
+                              "if pairing == \"interleaved\":\n        a, b = X[:, :d // 2], X[:, d // 2:]"),
+    "rope_frequency_exponent": ("return np.power(float(base), -2.0 * u / float(d))",
+                                "return np.power(float(base), -1.0 * u / float(d))"),
+    "rope_frequency_sign": ("return np.power(float(base), -2.0 * u / float(d))",
+                            "return np.power(float(base), 2.0 * u / float(d))"),
+    "rope_shift_reversed": ("rope_rotate(Ksel, slots - idx, base, pairing)", "rope_rotate(Ksel, idx - slots, base, pairing)"),
+    "rank_lowest_first": ("by_rank = np.argsort(-np.asarray(scores)[idx], kind=\"stable\")",
+                          "by_rank = np.argsort(np.asarray(scores)[idx], kind=\"stable\")"),
+    "slots_not_inverted": ("slots[by_rank] = np.arange(idx.shape[0], dtype=np.int64)",
+                           "slots[:] = by_rank"),
+    "values_not_permuted": ("Vout[slots] = Vsel", "Vout[:] = Vsel"),
     "dropped_scale": ("S = (Q @ K.T) / math.sqrt(float(d))", "S = (Q @ K.T)"),
     "scale_by_d": ("/ math.sqrt(float(d))", "/ float(d)"),
     "softmax_wrong_axis": ("mx = S.max(axis=1, keepdims=True)\n    E = np.exp(S - mx)\n    Z = E.sum(axis=1, keepdims=True)",
