@@ -92,6 +92,10 @@ def main() -> int:
                     help="launch path of the library (auto: its own choice)")
     ap.add_argument("--per-step", action="store_true",
                     help="one finch_step call per chunk instead of one finch_loop call")
+    ap.add_argument("--reposition", default="off", choices=["off", "half", "interleaved"],
+                    help="rotate kept keys to their new slots while compacting (rotary pairing)")
+    ap.add_argument("--order", default="ascending", choices=["ascending", "rank"],
+                    help="slots of the kept rows in the new cache")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -121,6 +125,10 @@ def main() -> int:
     fin = F.Finch(F.FINCH_BF16 if w.dtype == "bf16" else F.FINCH_F32, w.head_dim, w.group, device=dev)
     fin.set_step_path({"auto": F.FINCH_PATH_AUTO, "separate": F.FINCH_PATH_SEPARATE,
                        "owner": F.FINCH_PATH_OWNER}[args.path])
+
+    fin.set_reposition({"off": F.FINCH_ROPE_OFF, "half": F.FINCH_ROPE_HALF,
+                        "interleaved": F.FINCH_ROPE_INTERLEAVED}[args.reposition],
+                       {"ascending": F.FINCH_ORDER_ASCENDING, "rank": F.FINCH_ORDER_RANK}[args.order], 500000.0)
 
     t_gen = time.perf_counter()
     probs = []
@@ -203,6 +211,7 @@ def main() -> int:
                    "document_tokens": n_tokens, "chunk": w.chunk, "chunk_steps": loop.n_steps,
                    "head_dim": w.head_dim, "group": w.group,
                    "path": args.path, "calls": "finch_step per chunk" if args.per_step else "finch_loop",
+                   "reposition": args.reposition, "order": args.order,
                    "prompt_rows": [w.rows(r) for r in w.requests][:4],
                    "budget": [r.budget for r in w.requests][:4], "keys_scored": keys},
         "path": {"algorithmic_bytes": total_bytes, "achieved_GBps": path_gbps,

@@ -103,6 +103,33 @@ finch_status finch_compact(finch_ctx* ctx, const finch_problem* host_desc,
                            const finch_problem* dev_desc, int32_t n_problems,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/* Re-positioning (Method: Managing the Cache - the positional embedding of a kept
+ * pair is adjusted to the place it moves to; for rotary embeddings by rotating the
+ * key to the earlier or later position).  Once set on a context, the compaction of
+ * finch_compact, finch_step and finch_loop becomes
+ *   k_out[slot(t)] = Rot(K[idx[t]], slot(t) - idx[t]),  v_out[slot(t)] = V[idx[t]],
+ * t < min(r, c+m): a candidate's old position is its index in [cache ; chunk], its
+ * new one its slot.  Rot(x, s) turns channel pair u of x by the angle s * theta_u,
+ * theta_u = base^(-2u/d): pairs are (u, u + d/2) for FINCH_ROPE_HALF (the layout of
+ * Llama-style models) or (2u, 2u+1) for FINCH_ROPE_INTERLEAVED; FINCH_ROPE_OFF
+ * leaves keys as they are.  slot(t) = t for FINCH_ORDER_ASCENDING; for
+ * FINCH_ORDER_RANK the kept pairs are packed by relevance as in the paper's worked
+ * example: slot = rank of the score among the kept ones, highest first, equal
+ * scores by index (idx itself stays ascending; needs desc.scores in finch_compact
+ * and at most 32768 kept rows per problem, else FINCH_ERR_CAPACITY).  Rotation is
+ * computed in fp32 (angles reduced in fp64); bf16 results are rounded to nearest
+ * even; a shift of 0 leaves the key bit-identical.  NULL, or {OFF, ASCENDING},
+ * restores the plain copy.  While re-positioning is on, batches run with one kernel
+ * per stage (FINCH_PATH_OWNER is refused with FINCH_ERR_UNSUPPORTED). */
+typedef enum { FINCH_ROPE_OFF = 0, FINCH_ROPE_HALF = 1, FINCH_ROPE_INTERLEAVED = 2 } finch_rope_pairing;
+typedef enum { FINCH_ORDER_ASCENDING = 0, FINCH_ORDER_RANK = 1 } finch_order;
+typedef struct {
+  int32_t pairing; /* finch_rope_pairing */
+  int32_t order;   /* finch_order        */
+  double base;     /* rotary base (10000 for Llama 2); > 1 when pairing != OFF */
+} finch_reposition;
+finch_status finch_set_reposition(finch_ctx* ctx, const finch_reposition* how);
+
 /* One prefill step (Method: Document Segmentation - the pairs kept at step i-1
  * compete with chunk i): score, then top-r, then compaction, stream-ordered with
  * no host synchronisation.  desc.scores may be NULL. */

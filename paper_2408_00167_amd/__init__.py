@@ -30,7 +30,7 @@ EXPORTED_SYMBOLS = (
     "finch_create", "finch_destroy", "finch_workspace_size", "finch_score", "finch_topk",
     "finch_compact", "finch_step", "finch_schedule", "finch_last_hip_error",
     "finch_status_string", "finch_version", "finch_profile", "finch_profile_read",
-    "finch_set_option", "finch_loop", "finch_loop_workspace_size",
+    "finch_set_option", "finch_set_reposition", "finch_loop", "finch_loop_workspace_size",
 )
 
 KERNEL_NAMES = ("rowstats", "lse", "colsum", "select", "gather", "owner")
@@ -40,12 +40,18 @@ FINCH_OPT_SLICE_KEYS = 3
 FINCH_PATH_AUTO = 0
 FINCH_PATH_SEPARATE = 1
 FINCH_PATH_OWNER = 3
+FINCH_ROPE_OFF, FINCH_ROPE_HALF, FINCH_ROPE_INTERLEAVED = 0, 1, 2
+FINCH_ORDER_ASCENDING, FINCH_ORDER_RANK = 0, 1
 
 
 class FinchError(RuntimeError):
     def __init__(self, status: int, where: str, detail: str = ""):
         self.status = status
         super().__init__(f"{where}: status {status} ({detail})")
+
+
+class finch_reposition(ctypes.Structure):
+    _fields_ = [("pairing", ctypes.c_int32), ("order", ctypes.c_int32), ("base", ctypes.c_double)]
 
 
 class finch_config(ctypes.Structure):
@@ -101,6 +107,8 @@ def load_library() -> ctypes.CDLL:
     lib.finch_loop_workspace_size.restype = ctypes.c_int
     lib.finch_loop.argtypes = [vp, P(finch_problem), vp, P(i32), vp, i32, vp, sz, vp]
     lib.finch_loop.restype = ctypes.c_int
+    lib.finch_set_reposition.argtypes = [vp, P(finch_reposition)]
+    lib.finch_set_reposition.restype = ctypes.c_int
     lib.finch_set_option.argtypes = [vp, i32, i64]
     lib.finch_set_option.restype = ctypes.c_int
     lib.finch_version.argtypes = []
@@ -183,6 +191,12 @@ def finch_profile_read(ctx) -> Dict[str, Dict[str, float]]:
 
 def finch_set_option(ctx, option: int, value: int) -> None:
     _check(load_library().finch_set_option(ctx, option, value), "finch_set_option", ctx)
+
+
+def finch_set_reposition(ctx, pairing: int = FINCH_ROPE_OFF, order: int = FINCH_ORDER_ASCENDING,
+                         base: float = 10000.0) -> None:
+    how = finch_reposition(pairing, order, base)
+    _check(load_library().finch_set_reposition(ctx, ctypes.byref(how)), "finch_set_reposition", ctx)
 
 
 def finch_loop_workspace_size(ctx, host_desc, host_step_first, n_steps: int) -> int:
@@ -286,6 +300,10 @@ class Finch:
 
     def set_step_path(self, path: int) -> None:
         finch_set_option(self.ctx, FINCH_OPT_STEP_PATH, path)
+
+    def set_reposition(self, pairing: int = FINCH_ROPE_OFF, order: int = FINCH_ORDER_ASCENDING,
+                       base: float = 10000.0) -> None:
+        finch_set_reposition(self.ctx, pairing, order, base)
 
     def reserve(self, batch: Batch) -> int:
         import torch

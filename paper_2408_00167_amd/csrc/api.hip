@@ -23,6 +23,7 @@ struct finch_ctx {
   int n_cu;              // compute units of the device
   int step_path;         // FINCH_PATH_AUTO / _SEPARATE / _OWNER
   int slice_keys;        // target keys per workgroup slice of the bf16 scoring kernels
+  finch_reposition repos;  // {OFF, ASCENDING}: plain copies
 };
 
 namespace {
@@ -231,8 +232,12 @@ struct ProfScope {
 // One workgroup per problem pays when the problems fill the chip's CUs in whole
 // rounds (one 16-wave workgroup per CU at a time): AUTO takes that path when the
 // last round would be at least 85 % full.
+bool repositioning(const finch_ctx* ctx) {
+  return ctx->repos.pairing != FINCH_ROPE_OFF || ctx->repos.order != FINCH_ORDER_ASCENDING;
+}
+
 bool owner_wanted(const finch_ctx* ctx, const Plan& pl, int32_t n) {
-  if (!pl.own_ok || n <= 0) return false;
+  if (!pl.own_ok || n <= 0 || repositioning(ctx)) return false;
   if (ctx->step_path == FINCH_PATH_OWNER) return true;
   if (ctx->step_path != FINCH_PATH_AUTO) return false;
   const int64_t cu = ctx->n_cu > 0 ? ctx->n_cu : 256;
@@ -289,9 +294,14 @@ finch_status run_select(finch_ctx* ctx, const LaunchParams& p, hipStream_t s) {
 
 finch_status run_gather(finch_ctx* ctx, const LaunchParams& p, int r_max, hipStream_t s) {
   hipError_t e;
+  const bool rank = ctx->repos.order == FINCH_ORDER_RANK;
+  if (rank && r_max > finch::kRankMaxRows) return FINCH_ERR_CAPACITY;
   {
     ProfScope ps(ctx, FINCH_KERNEL_GATHER, s);
-    e = finch::launch_gather(p, ctx->row_bytes, r_max, s);
+    e = repositioning(ctx)
+            ? finch::launch_reposition(p, ctx->row_bytes, ctx->cfg.dtype == FINCH_BF16, r_max,
+                                       ctx->repos.pairing, rank, ctx->repos.base, s)
+            : finch::launch_gather(p, ctx->row_bytes, r_max, s);
   }
   return e == hipSuccess ? FINCH_OK : hip_fail(ctx, e);
 }
@@ -340,6 +350,9 @@ finch_status finch_create(const finch_config* cfg, finch_ctx** out) {
   ctx->n_cu = 0;
   ctx->step_path = FINCH_PATH_AUTO;
   ctx->slice_keys = finch::kDefaultSliceKeys;
+  ctx->repos.pairing = FINCH_ROPE_OFF;
+  ctx->repos.order = FINCH_ORDER_ASCENDING;
+  ctx->repos.base = 10000.0;
   hipError_t e = hipGetDevice(&ctx->device);
   if (e == hipSuccess) {
     int v = 0;
@@ -354,6 +367,8 @@ finch_status finch_create(const finch_config* cfg, finch_ctx** out) {
                                  : finch::set_max_lds_f32(ctx->max_lds);
   }
   if (e == hipSuccess && cfg->dtype == FINCH_BF16) e = finch::set_max_lds_owner(ctx->max_lds);
+  // the re-positioning kernel also has a little static LDS
+  if (e == hipSuccess) e = finch::set_max_lds_reposition(ctx->max_lds - 1024);
   if (e != hipSuccess) {
     // No usable GPU: there is no fallback path.  Report and hand nothing out.
     std::fprintf(stderr, "finch_create: HIP error %d (%s)\n", static_cast<int>(e),
@@ -387,6 +402,20 @@ finch_status finch_set_option(finch_ctx* ctx, int32_t option, int64_t value) {
     default:
       return FINCH_ERR_INVALID_ARG;
   }
+}
+
+finch_status finch_set_reposition(finch_ctx* ctx, const finch_reposition* how) {
+  if (!ctx) return FINCH_ERR_INVALID_ARG;
+  finch_reposition v = {FINCH_ROPE_OFF, FINCH_ORDER_ASCENDING, 10000.0};
+  if (how) v = *how;
+  if (v.pairing != FINCH_ROPE_OFF && v.pairing != FINCH_ROPE_HALF && v.pairing != FINCH_ROPE_INTERLEAVED)
+    return FINCH_ERR_INVALID_ARG;
+  if (v.order != FINCH_ORDER_ASCENDING && v.order != FINCH_ORDER_RANK) return FINCH_ERR_INVALID_ARG;
+  if (v.pairing != FINCH_ROPE_OFF && !(v.base > 1.0 && v.base < 1e30)) return FINCH_ERR_INVALID_ARG;
+  if (static_cast<size_t>(finch::kRankMaxRows) * 4 + 1024 > ctx->max_lds && v.order == FINCH_ORDER_RANK)
+    return FINCH_ERR_UNSUPPORTED;
+  ctx->repos = v;
+  return FINCH_OK;
 }
 
 finch_status finch_profile(finch_ctx* ctx, int32_t enable) {
@@ -478,7 +507,8 @@ finch_status finch_compact(finch_ctx* ctx, const finch_problem* host_desc,
   if (st != FINCH_OK) return st;
   Plan pl;
   if ((st = make_plan(ctx, host_desc, n, pl)) != FINCH_OK) return st;
-  if ((st = validate(ctx, host_desc, n, kNeedIdx | kNeedGather)) != FINCH_OK) return st;
+  const unsigned need_scores = ctx->repos.order == FINCH_ORDER_RANK ? kNeedScoresOut : 0u;
+  if ((st = validate(ctx, host_desc, n, kNeedIdx | kNeedGather | need_scores)) != FINCH_OK) return st;
   if ((st = check_workspace(pl, ws, ws_bytes)) != FINCH_OK) return st;
   if (n == 0 || pl.r_max == 0) return FINCH_OK;
   const LaunchParams p = make_params(ctx, dev_desc, n, pl, ws);

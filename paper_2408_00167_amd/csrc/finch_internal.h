@@ -22,8 +22,11 @@ __host__ __device__ inline int stream_slices(int n_keys, int slice_keys) {
 }
 // One-workgroup-per-problem path: most prompt rows staged per pass over the keys.
 constexpr int kOwnerMaxRowChunk = 256;
-// Rows copied by one workgroup of the compaction kernel.
+// Rows copied by one workgroup of the compaction kernels.
 constexpr int kGatherRows = 64;
+// Most kept rows per problem when slots go by score rank (their order keys are held
+// in LDS by every workgroup of the problem).
+constexpr int kRankMaxRows = 32768;
 
 // Everything the scoring / selection / compaction kernels need besides the
 // descriptors.  Passed by value.
@@ -57,6 +60,9 @@ hipError_t launch_lse(const LaunchParams& p, hipStream_t s);
 hipError_t launch_select(const LaunchParams& p, hipStream_t s);
 hipError_t launch_gather(const LaunchParams& p, int row_bytes, int r_max, hipStream_t s);
 size_t owner_lds_bytes(int head_dim, int row_chunk);
+hipError_t launch_reposition(const LaunchParams& p, int row_bytes, bool bf16, int r_max, int pairing,
+                             bool rank, double base, hipStream_t s);
+hipError_t set_max_lds_reposition(size_t bytes);
 hipError_t launch_owner_bf16(int head_dim, const LaunchParams& p, int stages, hipStream_t s);
 hipError_t launch_owner_loop_bf16(int head_dim, const LaunchParams& p, const int* step_first,
                                   int n_steps, int n_slots, hipStream_t s);

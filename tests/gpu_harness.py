@@ -151,9 +151,32 @@ def single_step_case(fin: F.Finch, specs: Sequence[Dict], dtype: torch.dtype, d:
     return F.Batch(descs), ts
 
 
-def validate_single_step(ts: Sequence[Dict], what: str, check_scores_too: bool = True) -> Dict:
+def check_repositioned(t: Dict, Kc, Kk, Vc, Vk, idx, rr, pairing, order, base, tag) -> float:
+    """K', V' of one problem against the oracle's re-positioned compaction.  Slots
+    by rank are decided from the scores the GPU itself holds (fp32), with the
+    oracle's rule; keys within rounding of the fp64 rotation; values bit for bit."""
+    Kout, Vout = W.to_numpy_storage(t["k_out"]), W.to_numpy_storage(t["v_out"])
+    gscores = t["scores"].cpu().numpy()[:t["c"] + t["m"]] if t["scores"] is not None else None
+    Kw, Vw, slots = O.compact_repositioned(idx[:rr], gscores, Kc, Kk, Vc, Vk, base, pairing, order)
+    assert Vout[:rr].tobytes() == Vw.tobytes(), f"{tag}: V rows"
+    got = O.widen(Kout[:rr])
+    rowmax = np.abs(Kw).max(axis=1, keepdims=True) if rr else np.zeros((0, 1))
+    rel = 0.004 if dtype_name(t["k_out"]) == "bf16" else 0.0
+    err = np.abs(got - Kw)
+    bound = rel * np.abs(Kw) + 1e-5 * rowmax
+    assert (err <= bound).all(), f"{tag}: re-positioned K off by {float((err - bound).max()):.3e}"
+    # a candidate that keeps its position keeps its bits
+    both = np.concatenate([Kc, Kk], axis=0)
+    for ti in np.nonzero(slots == idx[:rr])[0]:
+        assert Kout[slots[ti]].tobytes() == both[idx[ti]].tobytes(), f"{tag}: unmoved key changed"
+    return float((err / np.maximum(rowmax, 1e-30)).max()) if rr else 0.0
+
+
+def validate_single_step(ts: Sequence[Dict], what: str, check_scores_too: bool = True,
+                         repos=None) -> Dict:
+    """`repos` = (pairing or None, order, base) when re-positioning is switched on."""
     torch.cuda.synchronize()
-    stats = dict(swaps=0, worst_rel=0.0)
+    stats = dict(swaps=0, worst_rel=0.0, worst_rot=0.0)
     for n, t in enumerate(ts):
         tol = SCORE_TOL[dtype_name(t["q"])]
         N, r = t["c"] + t["m"], t["r"]
@@ -172,8 +195,12 @@ def validate_single_step(ts: Sequence[Dict], what: str, check_scores_too: bool =
         if rr == 0:
             assert idx[0] == -9
         Kout, Vout = W.to_numpy_storage(t["k_out"]), W.to_numpy_storage(t["v_out"])
-        assert Kout[:rr].tobytes() == O.gather_rows(idx[:rr], Kc, Kk).tobytes(), f"{tag}: K rows"
-        assert Vout[:rr].tobytes() == O.gather_rows(idx[:rr], Vc, Vk).tobytes(), f"{tag}: V rows"
+        if repos is None:
+            assert Kout[:rr].tobytes() == O.gather_rows(idx[:rr], Kc, Kk).tobytes(), f"{tag}: K rows"
+            assert Vout[:rr].tobytes() == O.gather_rows(idx[:rr], Vc, Vk).tobytes(), f"{tag}: V rows"
+        else:
+            stats["worst_rot"] = max(stats["worst_rot"],
+                                     check_repositioned(t, Kc, Kk, Vc, Vk, idx, rr, *repos, tag))
         guard = W.to_numpy_storage(torch.full((1, Kout.shape[1]), 7.0).to(t["k_out"].dtype))
         assert Kout[rr:].tobytes() == np.repeat(guard, Kout.shape[0] - rr, axis=0).tobytes(), \
             f"{tag}: rows beyond r were touched"
