@@ -44,6 +44,12 @@ t-th kept index in ascending order, or, as in the paper's worked example, the
 rank of its score among the kept ones (highest first, ties to the lower index);
 the rotary pairing is either (u, u + d/2) ("half", the Llama layout the paper
 names) or (2u, 2u+1) ("interleaved", RoFormer's own); theta_u = base^(-2u/d).
+The paper-exact denominator (`prompt_lse`, `key_scores(..., lse_extra=...)`): in
+the model the prompt rows' softmax also runs over the prompt's own keys, causally;
+the default reading leaves them out.  Pinned by the explicit attention matrix over
+[context ; prompt] columns with the causal mask written out, softmaxed by scipy,
+from which the context columns are cut.
+
 Pins: a rotation by zero is the identity bit for bit, rotations add up, pair norms
 are kept, dot products of two rotated vectors depend only on the difference of
 their positions, the closed form (1, 0) -> (cos a, sin a), numpy's complex
@@ -59,7 +65,7 @@ import numpy as np
 
 __all__ = ["widen", "attention_weights", "key_scores", "top_r", "gather_rows",
            "step", "schedule", "compress", "reposition", "rope_frequencies", "rope_rotate",
-           "kept_slots", "compact_repositioned"]
+           "kept_slots", "compact_repositioned", "prompt_lse"]
 
 
 def widen(x: np.ndarray) -> np.ndarray:
@@ -90,17 +96,50 @@ def attention_weights(Q: np.ndarray, K: np.ndarray) -> np.ndarray:
     return E / Z
 
 
-def key_scores(Q: np.ndarray, K_cache: np.ndarray, K_chunk: np.ndarray) -> np.ndarray:
+def key_scores(Q: np.ndarray, K_cache: np.ndarray, K_chunk: np.ndarray,
+               lse_extra: Optional[np.ndarray] = None) -> np.ndarray:
     """One relevance score per context key (Method: sum over heads, prompt-guided
     sub-matrix, aggregation over prompt rows).
 
     Keys are ordered cache rows first, then chunk rows.  Because Q already stacks
     the prompt rows of every head of the group, the head sum and the sum over
     prompt tokens are one column sum of the weight matrix.
+
+    lse_extra (one value per row of Q, natural log) widens every row's softmax by
+    keys that are not candidates: the row's weights over the context keys become
+    exp(s_ij) / (sum_j exp(s_ij) + exp(lse_extra_i)).  With `prompt_lse` this gives
+    the prompt-guided sub-matrix exactly as the model computes it, where a prompt
+    token also attends, causally, to the prompt itself.
     """
     K = np.concatenate([np.asarray(K_cache), np.asarray(K_chunk)], axis=0)
     P = attention_weights(Q, K)
+    if lse_extra is not None and P.shape[1] > 0:
+        Qw, Kw = widen(Q), widen(K)
+        S = (Qw @ Kw.T) / math.sqrt(float(Qw.shape[1]))
+        mx = S.max(axis=1)
+        lse_ctx = mx + np.log(np.exp(S - mx[:, None]).sum(axis=1))
+        share = 1.0 / (1.0 + np.exp(np.asarray(lse_extra, dtype=np.float64) - lse_ctx))
+        P = P * share[:, None]
     return P.sum(axis=0)
+
+
+def prompt_lse(Q: np.ndarray, K_que: np.ndarray, group: int) -> np.ndarray:
+    """log sum exp of each prompt row's logits over the prompt's own keys under the
+    causal mask (Method: the prompt follows the context in the model's input, so a
+    prompt token sees the context and the prompt tokens up to itself).  Q stacks
+    the `group` heads, n_que rows each; row g*n_que + t is token t and sees prompt
+    keys 0..t of K_que [n_que][d].  Natural log, float64.
+    """
+    Qw, Kw = widen(Q), widen(K_que)
+    n_que = Kw.shape[0]
+    assert Qw.shape[0] == group * n_que
+    S = (Qw @ Kw.T) / math.sqrt(float(Qw.shape[1]))
+    out = np.empty(Qw.shape[0], dtype=np.float64)
+    for row in range(Qw.shape[0]):
+        t = row % n_que
+        s = S[row, :t + 1]
+        out[row] = s.max() + math.log(np.exp(s - s.max()).sum())
+    return out
 
 
 def top_r(scores: np.ndarray, r: int) -> np.ndarray:

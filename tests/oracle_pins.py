@@ -473,4 +473,41 @@ def pin_compact_repositioned(O):
     assert ((s2 - idx) <= 0).all()
 
 
+def pin_paper_exact_denominator(O):
+    """The prompt-guided sub-matrix as the model forms it: softmax over context AND
+    (causally) prompt keys, then the context columns.  Built here with an explicit
+    mask and scipy's softmax."""
+    from scipy.special import softmax
+    rng = np.random.default_rng(41)
+    d, G, nq, c, m = 16, 3, 5, 4, 7
+    Q = rng.standard_normal((G * nq, d)).astype(np.float32)
+    Kq = rng.standard_normal((nq, d)).astype(np.float32)
+    Kc = rng.standard_normal((c, d)).astype(np.float32)
+    Kk = rng.standard_normal((m, d)).astype(np.float32)
+    allk = np.concatenate([Kc, Kk, Kq]).astype(np.float64)
+    S = Q.astype(np.float64) @ allk.T / math.sqrt(d)
+    for row in range(G * nq):
+        t = row % nq
+        S[row, c + m + t + 1:] = -np.inf          # prompt keys after the token itself
+    A = softmax(S, axis=1)
+    want = A[:, :c + m].sum(axis=0)
+    extra = O.prompt_lse(Q, Kq, G)
+    got = O.key_scores(Q, Kc, Kk, lse_extra=extra)
+    assert np.abs(got - want).max() < 1e-13
+    # the prompt's share is gone from the total: sum < R, and by exactly that share
+    assert abs(got.sum() - (G * nq - A[:, c + m:].sum())) < 1e-12
+    # first token of every head sees only its own key among the prompt keys
+    for g in range(G):
+        q0 = Q[g * nq].astype(np.float64)
+        assert abs(extra[g * nq] - q0 @ Kq[0].astype(np.float64) / math.sqrt(d)) < 1e-13
+    # no extra keys (lse_extra = -inf) is the default reading
+    base = O.key_scores(Q, Kc, Kk)
+    same = O.key_scores(Q, Kc, Kk, lse_extra=np.full(G * nq, -np.inf))
+    assert np.abs(base - same).max() < 1e-15
+    # one prompt row: the extra keys scale every score by one factor, ranking unchanged
+    one = O.key_scores(Q[:1], Kc, Kk, lse_extra=extra[:1])
+    ref = O.key_scores(Q[:1], Kc, Kk)
+    assert np.abs(one / ref - (one / ref)[0]).max() < 1e-13 and (one < ref).all()
+
+
 ALL_PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_") and callable(v)]

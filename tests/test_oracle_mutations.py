@@ -14,6 +14,12 @@ SRC = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
                    "oracle", "finch_oracle.py")
 
 MUTATIONS = {
+    "extra_keys_not_causal": ("s = S[row, :t + 1]", "s = S[row, :]"),
+    "extra_keys_exclude_self": ("s = S[row, :t + 1]", "s = S[row, :max(t, 1)]"),
+    "extra_rows_token_major": ("t = row % n_que\n        s = S[row", "t = row // group\n        s = S[row"),
+    "extra_share_inverted": ("share = 1.0 / (1.0 + np.exp(np.asarray(lse_extra, dtype=np.float64) - lse_ctx))",
+                             "share = 1.0 / (1.0 + np.exp(lse_ctx - np.asarray(lse_extra, dtype=np.float64)))"),
+    "extra_share_ignored": ("P = P * share[:, None]", "P = P"),
     "rope_sine_sign": ("out = np.concatenate([a * cs - b * sn, b * cs + a * sn], axis=1)",
                        "out = np.concatenate([a * cs + b * sn, b * cs - a * sn], axis=1)"),
     "rope_interleaved_sine_sign": ("out[:, 0::2] = a * cs - b * sn\n        out[:, 1::2] = b * cs + a * sn",
