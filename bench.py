@@ -96,6 +96,8 @@ def main() -> int:
                     help="rotate kept keys to their new slots while compacting (rotary pairing)")
     ap.add_argument("--order", default="ascending", choices=["ascending", "rank"],
                     help="slots of the kept rows in the new cache")
+    ap.add_argument("--exact-denominator", action="store_true",
+                    help="softmax denominators include the prompt's own keys (random ones here)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -136,6 +138,8 @@ def main() -> int:
         p = W.make_problem(w, b, l, g, device=dev)
         probs.append(dict(Q=p["Q"], K=p["K"], V=p["V"], n_que=w.requests[b].n_que,
                           budget=w.requests[b].budget))
+        if args.exact_denominator:
+            probs[-1]["K_que"] = torch.randn(w.requests[b].n_que, w.head_dim, device=dev).to(p["K"].dtype)
     loop = ChunkLoop(fin, probs, w.chunk, history=False, want_scores=False)
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
@@ -185,7 +189,8 @@ def main() -> int:
                 kernels[name] = dict(avg_us=1e3 * v["ms"] / v["launches"], launches_per_step=v["launches"] // prof_steps,
                                      ms_per_step=v["ms"] / prof_steps)
         dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
-        klass = {"rowstats": "score_pass", "colsum": "score_pass", "owner": "step",
+        per_kernel_bytes["prompt_lse"] = 0
+        klass = {"prompt_lse": "prompt_lse","rowstats": "score_pass", "colsum": "score_pass", "owner": "step",
                  "select": "select", "gather": "gather", "lse": "select"}[dom]
         launches = kernels[dom]["launches_per_step"]
         # a launch that runs all stages: everything the method has to move (keys once)
@@ -212,6 +217,7 @@ def main() -> int:
                    "head_dim": w.head_dim, "group": w.group,
                    "path": args.path, "calls": "finch_step per chunk" if args.per_step else "finch_loop",
                    "reposition": args.reposition, "order": args.order,
+                   "exact_denominator": args.exact_denominator,
                    "prompt_rows": [w.rows(r) for r in w.requests][:4],
                    "budget": [r.budget for r in w.requests][:4], "keys_scored": keys},
         "path": {"algorithmic_bytes": total_bytes, "achieved_GBps": path_gbps,

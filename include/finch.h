@@ -66,6 +66,11 @@ typedef struct {
   int32_t c;           /* cache rows, >= 0                                            */
   int32_t m;           /* chunk rows, >= 0 (m == 0: a cache-only step)                */
   int32_t r;           /* rows to keep, >= 0; values above c+m mean "keep all"        */
+  const void* k_que;   /* [n_que][d] the prompt's own keys for this KV head; read only
+                          by finch_prompt_lse, may be NULL everywhere else            */
+  float* lse_extra;    /* [G*n_que] natural-log log-sum-exp, per prompt row, of logits
+                          over keys that are not candidates; NULL = none.  Written by
+                          finch_prompt_lse, read by the scoring of every other call   */
 } finch_problem;
 
 /* Row bases (q, k_*, v_*, *_out) must be 16-byte aligned, scores and idx 4-byte. */
@@ -83,10 +88,21 @@ finch_status finch_workspace_size(const finch_ctx* ctx, const finch_problem* hos
  * over the heads of the group and over the prompt rows):
  *   scores[j] = sum_{i<R} softmax_j( q_i . k_j / sqrt(d_k) ),  j < c+m,
  * the softmax running over the c+m context keys, so sum_j scores[j] == R.
- * Writes desc.scores (must be non-NULL here). */
+ * Writes desc.scores (must be non-NULL here).  (See below for desc.lse_extra.) */
 finch_status finch_score(finch_ctx* ctx, const finch_problem* host_desc,
                          const finch_problem* dev_desc, int32_t n_problems,
                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* The paper-exact denominator.  With desc.lse_extra the denominator of row i is widened to
+ *   sum_j exp(s_ij) + exp(lse_extra[i]):
+ * the weights of the prompt-guided sub-matrix exactly as the model forms them, where
+ * (Method: the prompt follows the chunk in the input) a prompt token also attends to
+ * the prompt tokens up to itself.  Then sum_j scores[j] < R.  finch_prompt_lse
+ * computes that term: lse_extra[g*n_que + t] = log sum_{j<=t} exp(q_{g,t} . kq_j /
+ * sqrt(d_k)) over the prompt keys desc.k_que (causal).  It reads desc.q, desc.k_que
+ * and n_que and writes desc.lse_extra (all three required); no workspace. */
+finch_status finch_prompt_lse(finch_ctx* ctx, const finch_problem* host_desc,
+                              const finch_problem* dev_desc, int32_t n_problems, void* stream);
 
 /* Selection (Method: t = top-r(A_agg, r)): reads desc.scores (any finite fp32),
  * writes the indices of the min(r, c+m) largest into desc.idx in ascending order;
@@ -199,7 +215,8 @@ typedef enum {
   FINCH_KERNEL_SELECT = 3,   /* top-r                                        */
   FINCH_KERNEL_GATHER = 4,   /* compaction                                   */
   FINCH_KERNEL_OWNER = 5,    /* all stages, one workgroup per problem        */
-  FINCH_KERNEL_COUNT = 6
+  FINCH_KERNEL_PROMPT_LSE = 6, /* finch_prompt_lse                             */
+  FINCH_KERNEL_COUNT = 7
 } finch_kernel;
 finch_status finch_profile(finch_ctx* ctx, int32_t enable);
 finch_status finch_profile_read(finch_ctx* ctx, float* ms, int32_t* launches);

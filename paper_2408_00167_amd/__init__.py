@@ -30,10 +30,10 @@ EXPORTED_SYMBOLS = (
     "finch_create", "finch_destroy", "finch_workspace_size", "finch_score", "finch_topk",
     "finch_compact", "finch_step", "finch_schedule", "finch_last_hip_error",
     "finch_status_string", "finch_version", "finch_profile", "finch_profile_read",
-    "finch_set_option", "finch_set_reposition", "finch_loop", "finch_loop_workspace_size",
+    "finch_set_option", "finch_set_reposition", "finch_prompt_lse", "finch_loop", "finch_loop_workspace_size",
 )
 
-KERNEL_NAMES = ("rowstats", "lse", "colsum", "select", "gather", "owner")
+KERNEL_NAMES = ("rowstats", "lse", "colsum", "select", "gather", "owner", "prompt_lse")
 
 FINCH_OPT_STEP_PATH = 1
 FINCH_OPT_SLICE_KEYS = 3
@@ -65,7 +65,7 @@ class finch_problem(ctypes.Structure):
                 ("k_out", ctypes.c_void_p), ("v_out", ctypes.c_void_p),
                 ("scores", ctypes.c_void_p), ("idx", ctypes.c_void_p),
                 ("n_que", ctypes.c_int32), ("c", ctypes.c_int32), ("m", ctypes.c_int32),
-                ("r", ctypes.c_int32)]
+                ("r", ctypes.c_int32), ("k_que", ctypes.c_void_p), ("lse_extra", ctypes.c_void_p)]
 
 
 _lib = None
@@ -107,6 +107,8 @@ def load_library() -> ctypes.CDLL:
     lib.finch_loop_workspace_size.restype = ctypes.c_int
     lib.finch_loop.argtypes = [vp, P(finch_problem), vp, P(i32), vp, i32, vp, sz, vp]
     lib.finch_loop.restype = ctypes.c_int
+    lib.finch_prompt_lse.argtypes = [vp, P(finch_problem), vp, i32, vp]
+    lib.finch_prompt_lse.restype = ctypes.c_int
     lib.finch_set_reposition.argtypes = [vp, P(finch_reposition)]
     lib.finch_set_reposition.restype = ctypes.c_int
     lib.finch_set_option.argtypes = [vp, i32, i64]
@@ -152,6 +154,11 @@ def _call(name: str, ctx, host_desc, dev_desc_ptr: int, n: int, ws_ptr: int, ws_
     fn = getattr(load_library(), name)
     _check(fn(ctx, host_desc, ctypes.c_void_p(dev_desc_ptr), n, ctypes.c_void_p(ws_ptr),
               ws_bytes, ctypes.c_void_p(stream)), name, ctx)
+
+
+def finch_prompt_lse(ctx, host_desc, dev_desc_ptr: int, n: int, stream: int = 0) -> None:
+    _check(load_library().finch_prompt_lse(ctx, host_desc, ctypes.c_void_p(dev_desc_ptr), n,
+                                           ctypes.c_void_p(stream)), "finch_prompt_lse", ctx)
 
 
 def finch_score(ctx, host_desc, dev_desc_ptr, n, ws_ptr, ws_bytes, stream=0):
@@ -234,8 +241,8 @@ class Batch:
     """A descriptor array on the host and its copy on the device.
 
     `problems` is a sequence of dicts with tensors q, k_cache, v_cache, k_chunk,
-    v_chunk, k_out, v_out, scores, idx (any may be None where the C ABI allows
-    NULL) and ints n_que, c, m, r.  The tensors are only read for their device
+    v_chunk, k_out, v_out, scores, idx, and optionally k_que, lse_extra (any may be
+    None where the C ABI allows NULL) and ints n_que, c, m, r.  The tensors are only read for their device
     pointers; the caller keeps them alive.
     """
 
@@ -247,7 +254,7 @@ class Batch:
         for i, pb in enumerate(problems):
             d = self.host[i]
             for name in ("q", "k_cache", "v_cache", "k_chunk", "v_chunk", "k_out", "v_out",
-                         "scores", "idx"):
+                         "scores", "idx", "k_que", "lse_extra"):
                 setattr(d, name, _ptr(pb.get(name)))
             d.n_que, d.c, d.m, d.r = int(pb["n_que"]), int(pb["c"]), int(pb["m"]), int(pb["r"])
         raw = bytes(self.host)[: n * ctypes.sizeof(finch_problem)]
@@ -330,6 +337,11 @@ class Finch:
 
     def step(self, batch: Batch, stream=None):
         self._run("finch_step", batch, stream)
+
+    def prompt_lse(self, batch: Batch, stream=None):
+        import torch
+        s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
+        finch_prompt_lse(self.ctx, batch.host, batch.dev_ptr, batch.n, s)
 
     def reserve_loop(self, lb: LoopBatch) -> int:
         import torch

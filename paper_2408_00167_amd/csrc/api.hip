@@ -141,6 +141,7 @@ finch_status validate(const finch_ctx* ctx, const finch_problem* hd, int32_t n, 
       if (!pb.scores) return FINCH_ERR_INVALID_ARG;
     }
     if (pb.scores && !aligned(pb.scores, 4)) return FINCH_ERR_INVALID_ARG;
+    if (pb.lse_extra && !aligned(pb.lse_extra, 4)) return FINCH_ERR_INVALID_ARG;
     if ((need & kNeedIdx) && rr > 0) {
       if (!pb.idx || !aligned(pb.idx, 4)) return FINCH_ERR_INVALID_ARG;
     }
@@ -484,6 +485,30 @@ finch_status finch_score(finch_ctx* ctx, const finch_problem* host_desc,
   if ((st = check_workspace(pl, ws, ws_bytes)) != FINCH_OK) return st;
   const LaunchParams p = make_params(ctx, dev_desc, n, pl, ws);
   return run_score(ctx, p, pl, static_cast<hipStream_t>(stream));
+}
+
+finch_status finch_prompt_lse(finch_ctx* ctx, const finch_problem* host_desc,
+                              const finch_problem* dev_desc, int32_t n, void* stream) {
+  finch_status st = check_common(ctx, host_desc, dev_desc, n);
+  if (st != FINCH_OK) return st;
+  Plan pl;
+  if ((st = make_plan(ctx, host_desc, n, pl)) != FINCH_OK) return st;
+  for (int32_t i = 0; i < n; ++i) {
+    const finch_problem& pb = host_desc[i];
+    if (!pb.q || !aligned(pb.q, 16) || !pb.k_que || !aligned(pb.k_que, 16) || !pb.lse_extra ||
+        !aligned(pb.lse_extra, 4))
+      return FINCH_ERR_INVALID_ARG;
+  }
+  if (n == 0) return FINCH_OK;
+  if (static_cast<int64_t>(n) * ((pl.rows_max + 255) / 256) >= (int64_t{1} << 31)) return FINCH_ERR_CAPACITY;
+  const LaunchParams p = make_params(ctx, dev_desc, n, pl, nullptr);
+  hipError_t e;
+  {
+    ProfScope ps(ctx, FINCH_KERNEL_PROMPT_LSE, static_cast<hipStream_t>(stream));
+    e = finch::launch_prompt_lse(p, ctx->cfg.head_dim, ctx->cfg.dtype == FINCH_BF16, pl.rows_max,
+                                 static_cast<hipStream_t>(stream));
+  }
+  return e == hipSuccess ? FINCH_OK : hip_fail(ctx, e);
 }
 
 finch_status finch_topk(finch_ctx* ctx, const finch_problem* host_desc,

@@ -60,6 +60,7 @@ hipError_t launch_lse(const LaunchParams& p, hipStream_t s);
 hipError_t launch_select(const LaunchParams& p, hipStream_t s);
 hipError_t launch_gather(const LaunchParams& p, int row_bytes, int r_max, hipStream_t s);
 size_t owner_lds_bytes(int head_dim, int row_chunk);
+hipError_t launch_prompt_lse(const LaunchParams& p, int head_dim, bool bf16, int rows_max, hipStream_t s);
 hipError_t launch_reposition(const LaunchParams& p, int row_bytes, bool bf16, int r_max, int pairing,
                              bool rank, double base, hipStream_t s);
 hipError_t set_max_lds_reposition(size_t bytes);

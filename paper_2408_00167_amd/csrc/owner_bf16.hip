@@ -204,6 +204,7 @@ __device__ __forceinline__ void own_step_body(const LaunchParams& prm, const fin
           merge_stats(a.x, a.y, c.x, c.y);
         }
         l = a.x + fast_log2(a.y);
+        if (pb.lse_extra) l = widen_lse(l, as_global<float>(pb.lse_extra)[row0 + i]);
       }
       lds_lse[i] = l;
     }

@@ -225,6 +225,7 @@ __global__ __launch_bounds__(kThreads, 4) void colsum_bf16(LaunchParams prm) {
             merge_stats(m, z, s2.x, s2.y);
           }
           l = m + fast_log2(z);
+          if (pb.lse_extra) l = widen_lse(l, as_global<float>(pb.lse_extra)[row0 + i]);
         }
         lds_lse[i] = l;
       }
@@ -298,6 +299,7 @@ __global__ __launch_bounds__(256) void lse_merge(LaunchParams prm) {
         merge_stats(m, z, s.x, s.y);
       }
       out = m + fast_log2(z);
+      if (pb.lse_extra) out = widen_lse(out, as_global<float>(pb.lse_extra)[row]);
     }
     lse[row] = out;
   }

@@ -28,6 +28,15 @@ __device__ __forceinline__ void merge_stats(float& m, float& z, float m2, float 
   m = mm;
 }
 
+// log2-domain log-sum-exp of a row widened by keys outside the candidates whose
+// natural-log log-sum-exp is extra_ln (-inf: none).
+__device__ __forceinline__ float widen_lse(float lse2, float extra_ln) {
+  const float e2 = extra_ln * 1.4426950408889634f;
+  const float mx = fmaxf(lse2, e2);
+  if (mx == -kInf) return lse2;
+  return mx + fast_log2(fast_exp2(lse2 - mx) + fast_exp2(e2 - mx));
+}
+
 // Key (row of the 32x32 logit block) held in accumulator register v of a lane in
 // lane-half h.
 __device__ __forceinline__ int acc_key(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }

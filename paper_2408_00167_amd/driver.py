@@ -26,6 +26,9 @@ class ChunkLoop:
         K, V    [n_cont][d] document keys / values (device tensors)
         n_que   prompt rows per query head (R = group * n_que)
         budget  k, rows to keep at the end
+        K_que   optional: [n_que][d] the prompt's own keys (or a list, one per step):
+                the softmax denominators then include them (finch_prompt_lse runs
+                at the start of `run`)
     chunk: m, document rows per step.
     history: keep the scores and indices of every step (tests); otherwise one
         scores/idx buffer is reused by all steps.
@@ -73,6 +76,16 @@ class ChunkLoop:
         self.scores = (torch.zeros(n_hist, max(1, self.n_off[-1]), dtype=torch.float32, device=dev)
                        if self.want_scores else None)
         self.idx = torch.zeros(n_hist, max(1, tot_cap), dtype=torch.int32, device=dev)
+        # per-row term of the prompt's own keys: one slab per problem, per step if
+        # the prompt changes from step to step
+        self.exact = any(pb.get("K_que") is not None for pb in self.problems)
+        self.per_step_prompt = any(isinstance(pb["Q"], (list, tuple)) for pb in self.problems)
+        self.row_off = [0]
+        for pb in self.problems:
+            q0 = pb["Q"][0] if isinstance(pb["Q"], (list, tuple)) else pb["Q"]
+            self.row_off.append(self.row_off[-1] + int(q0.shape[0]))
+        self.lse_extra = (torch.zeros(self.n_steps if self.per_step_prompt else 1, max(1, self.row_off[-1]),
+                                      dtype=torch.float32, device=dev) if self.exact else None)
         self.batches: List[Batch] = []
         self.active: List[List[int]] = []
         self.step_shapes: List[List[tuple]] = []
@@ -94,8 +107,14 @@ class ChunkLoop:
                 src, dst = i % 2, (i + 1) % 2
                 o = self.cap_off[p]
                 q = pb["Q"][i] if isinstance(pb["Q"], (list, tuple)) else pb["Q"]
+                kq = pb.get("K_que")
+                kq = kq[i] if isinstance(kq, (list, tuple)) else kq
+                extra = None
+                if kq is not None:
+                    extra = self.lse_extra[i if self.per_step_prompt else 0,
+                                           self.row_off[p]:self.row_off[p + 1]]
                 descs.append(dict(
-                    q=q,
+                    q=q, k_que=kq, lse_extra=extra,
                     k_cache=self.kbuf[src][o:o + c], v_cache=self.vbuf[src][o:o + c],
                     k_chunk=pb["K"][lo:hi], v_chunk=pb["V"][lo:hi],
                     k_out=self.kbuf[dst][o:o + max(r, 1)], v_out=self.vbuf[dst][o:o + max(r, 1)],
@@ -117,6 +136,10 @@ class ChunkLoop:
     def run(self, stream: Optional[int] = None, per_step: bool = False) -> None:
         """Enqueue the whole loop - one finch_loop call, or with `per_step` one
         finch_step call per chunk; returns without synchronising."""
+        if self.exact:
+            # every problem is present at step 0; later steps only need it if their prompt differs
+            for b in (self.batches if self.per_step_prompt else self.batches[:1]):
+                self.fin.prompt_lse(b, stream)
         if per_step:
             for b in self.batches:
                 self.fin.step(b, stream)

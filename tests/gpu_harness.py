@@ -89,7 +89,15 @@ def validate_chunk_loop(loop: ChunkLoop, check: Sequence[int], what: str = "") -
         for i, r in enumerate(loop.rs[p]):
             lo, hi = i * loop.chunk, min((i + 1) * loop.chunk, loop.n_cont[p])
             q = pb["Q"][i] if isinstance(pb["Q"], (list, tuple)) else pb["Q"]
-            want_scores = O.key_scores(W.to_numpy_storage(q), Kc, Kd[lo:hi])
+            extra = None
+            if pb.get("K_que") is not None:
+                # checked against the oracle here, then used as the GPU holds it (fp32)
+                kq = pb["K_que"][i] if isinstance(pb["K_que"], (list, tuple)) else pb["K_que"]
+                extra = loop.lse_extra[i if loop.per_step_prompt else 0,
+                                       loop.row_off[p]:loop.row_off[p + 1]].double().cpu().numpy()
+                ref = O.prompt_lse(W.to_numpy_storage(q), W.to_numpy_storage(kq), q.shape[0] // pb["n_que"])
+                assert np.abs(extra - ref).max() < 1e-5 * max(1.0, np.abs(ref).max()), f"{what}: lse_extra"
+            want_scores = O.key_scores(W.to_numpy_storage(q), Kc, Kd[lo:hi], lse_extra=extra)
             g_scores, g_idx = loop.step_outputs(i, p)
             g_scores, g_idx = g_scores.cpu().numpy(), g_idx.cpu().numpy()
             tag = f"{what} problem {pb.get('id', p)} step {i}"
@@ -133,6 +141,10 @@ def single_step_case(fin: F.Finch, specs: Sequence[Dict], dtype: torch.dtype, d:
             scores=None if null_scores else torch.full((max(N, 1) + 1,), -5.0, device="cuda"),
             idx=torch.full((max(rr, 1) + 1,), -9, dtype=torch.int32, device="cuda"),
             n_que=sp["n_que"], c=c, m=m, r=r)
+        if sp.get("prompt_keys"):
+            # the prompt's own keys and room for the per-row term they add to the denominator
+            t["k_que"] = rand_storage((sp["n_que"], d), dtype, gen, sp.get("qscale", 1.0))
+            t["lse_extra"] = torch.full((R + 1,), -77.0, device="cuda")
         if "kramp" in sp and m > 0:
             # key magnitudes change steadily along the chunk (from 1x to kramp x)
             ramp = torch.logspace(0.0, float(np.log10(sp["kramp"])), m, device="cuda").unsqueeze(1)
@@ -147,6 +159,8 @@ def single_step_case(fin: F.Finch, specs: Sequence[Dict], dtype: torch.dtype, d:
         dsc["idx"] = t["idx"][:max(rr, 1)]
         if t["scores"] is not None:
             dsc["scores"] = t["scores"][:max(N, 1)]
+        if t.get("lse_extra") is not None:
+            dsc["lse_extra"] = t["lse_extra"][:-1]
         descs.append(dsc)
     return F.Batch(descs), ts
 
@@ -183,7 +197,12 @@ def validate_single_step(ts: Sequence[Dict], what: str, check_scores_too: bool =
         rr = min(r, N)
         Kc, Kk = W.to_numpy_storage(t["k_cache"]), W.to_numpy_storage(t["k_chunk"])
         Vc, Vk = W.to_numpy_storage(t["v_cache"]), W.to_numpy_storage(t["v_chunk"])
-        want = O.key_scores(W.to_numpy_storage(t["q"]), Kc, Kk)
+        extra = None
+        if t.get("lse_extra") is not None:
+            # the scoring is checked with the term the GPU was given (itself checked apart)
+            extra = t["lse_extra"][:-1].double().cpu().numpy()
+            assert float(t["lse_extra"][-1]) == -77.0, "wrote past the end of lse_extra"
+        want = O.key_scores(W.to_numpy_storage(t["q"]), Kc, Kk, lse_extra=extra)
         tag = f"{what} problem {n} (n_que={t['n_que']}, c={t['c']}, m={t['m']}, r={r})"
         if check_scores_too and t["scores"] is not None:
             got = t["scores"].cpu().numpy()
