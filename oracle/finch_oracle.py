@@ -50,6 +50,13 @@ the default reading leaves them out.  Pinned by the explicit attention matrix ov
 [context ; prompt] columns with the causal mask written out, softmaxed by scipy,
 from which the context columns are cut.
 
+Layer-wise selection as the paper words it (`layer_scores`, `step_layer`: the
+scores of all heads of a layer are summed and one index set serves every head) and
+the constant-budget schedule (`schedule(..., constant_budget=True)`).  Pinned by a
+pure-Python triple loop over heads, rows and keys, by a construction in which the
+heads disagree and the layer's choice is known in closed form, by H identical heads
+reproducing the single-head choice, and by closed forms of the schedule.
+
 Pins: a rotation by zero is the identity bit for bit, rotations add up, pair norms
 are kept, dot products of two rotated vectors depend only on the difference of
 their positions, the closed form (1, 0) -> (cos a, sin a), numpy's complex
@@ -65,7 +72,7 @@ import numpy as np
 
 __all__ = ["widen", "attention_weights", "key_scores", "top_r", "gather_rows",
            "step", "schedule", "compress", "reposition", "rope_frequencies", "rope_rotate",
-           "kept_slots", "compact_repositioned", "prompt_lse"]
+           "kept_slots", "compact_repositioned", "prompt_lse", "layer_scores", "step_layer"]
 
 
 def widen(x: np.ndarray) -> np.ndarray:
@@ -170,9 +177,12 @@ def step(Q, K_cache, V_cache, K_chunk, V_chunk, r: int):
     return scores, idx, gather_rows(idx, K_cache, K_chunk), gather_rows(idx, V_cache, V_chunk)
 
 
-def schedule(n_cont: int, m: int, k: int) -> List[int]:
+def schedule(n_cont: int, m: int, k: int, constant_budget: bool = False) -> List[int]:
     """Rows kept after each chunk step (Method: the r update rule; the last value
-    is the target size k, or n_cont if the budget is not smaller)."""
+    is the target size k, or n_cont if the budget is not smaller).  With
+    `constant_budget` every step keeps the full budget k as soon as that many
+    candidates exist ("top-k under the budget" read literally) instead of growing
+    r in proportion to the tokens seen."""
     if n_cont <= 0:
         return []
     out: List[int] = []
@@ -182,7 +192,7 @@ def schedule(n_cont: int, m: int, k: int) -> List[int]:
     while seen < n_cont:
         mi = min(m, n_cont - seen)
         seen += mi
-        r = min(c + mi, (k * seen) // n_cont)
+        r = min(c + mi, k if constant_budget else (k * seen) // n_cont)
         out.append(r)
         c = r
     return out
@@ -284,3 +294,29 @@ def compact_repositioned(idx, scores, K_cache, K_chunk, V_cache, V_chunk, base: 
     Kout[slots] = Krot
     Vout[slots] = Vsel
     return Kout, Vout, slots
+
+
+def layer_scores(per_head: Sequence[np.ndarray]) -> np.ndarray:
+    """The paper's layer-wise aggregate (Method: "Sum over heads" - the attention
+    of ALL heads of a layer is added up before one top-r per layer): the per-key
+    scores of the layer's KV heads, each already summed over its own query heads
+    and prompt rows, added up head by head."""
+    total = np.zeros_like(np.asarray(per_head[0], dtype=np.float64))
+    for s in per_head:
+        total = total + np.asarray(s, dtype=np.float64)
+    return total
+
+
+def step_layer(Qs, K_caches, V_caches, K_chunks, V_chunks, r: int, lse_extras=None):
+    """One prefill step of one layer with the paper's layer-wise selection: every KV
+    head h (own Q block, own keys and values, the same c and m) is scored, the
+    scores are summed over the heads, ONE index set is chosen and every head keeps
+    those positions.  Returns (per-head scores, layer scores, idx, [K'_h], [V'_h])."""
+    H = len(Qs)
+    per_head = [key_scores(Qs[h], K_caches[h], K_chunks[h],
+                           None if lse_extras is None else lse_extras[h]) for h in range(H)]
+    total = layer_scores(per_head)
+    idx = top_r(total, r)
+    return (per_head, total, idx,
+            [gather_rows(idx, K_caches[h], K_chunks[h]) for h in range(H)],
+            [gather_rows(idx, V_caches[h], V_chunks[h]) for h in range(H)])

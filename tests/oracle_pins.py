@@ -510,4 +510,60 @@ def pin_paper_exact_denominator(O):
     assert np.abs(one / ref - (one / ref)[0]).max() < 1e-13 and (one < ref).all()
 
 
+def pin_layer_wise_selection(O):
+    rng = np.random.default_rng(51)
+    d, H, nq, c, m, r = 8, 3, 2, 3, 5, 4
+    Qs = [rng.standard_normal((nq, d)).astype(np.float32) for _ in range(H)]
+    Kc = [rng.standard_normal((c, d)).astype(np.float32) for _ in range(H)]
+    Kk = [rng.standard_normal((m, d)).astype(np.float32) for _ in range(H)]
+    Vc = [rng.standard_normal((c, d)).astype(np.float32) for _ in range(H)]
+    Vk = [rng.standard_normal((m, d)).astype(np.float32) for _ in range(H)]
+    per_head, total, idx, Ks, Vs = O.step_layer(Qs, Kc, Vc, Kk, Vk, r)
+    # brute force: plain loops over heads, prompt rows and keys
+    want = [0.0] * (c + m)
+    for h in range(H):
+        keys = [list(map(float, row)) for row in np.concatenate([Kc[h], Kk[h]])]
+        for i in range(nq):
+            q = list(map(float, Qs[h][i]))
+            logits = [sum(a * b for a, b in zip(q, k)) / math.sqrt(d) for k in keys]
+            mx = max(logits)
+            e = [math.exp(x - mx) for x in logits]
+            z = sum(e)
+            for j in range(c + m):
+                want[j] += e[j] / z
+    assert max(abs(a - b) for a, b in zip(total, want)) < 1e-12
+    assert abs(total.sum() - H * nq) < 1e-12
+    order = sorted(range(c + m), key=lambda j: (-want[j], j))[:r]
+    assert idx.tolist() == sorted(order)
+    for h in range(H):      # every head keeps the SAME positions of its own rows
+        allk, allv = np.concatenate([Kc[h], Kk[h]]), np.concatenate([Vc[h], Vk[h]])
+        assert Ks[h].tobytes() == allk[idx].tobytes() and Vs[h].tobytes() == allv[idx].tobytes()
+    # heads that disagree: head 0 puts all its weight on key 0, heads 1 and 2 put 0.6 of
+    # theirs on key 1 and the rest on key 2; the layer keeps key 1 (1.2) over key 0 (1.0),
+    # although head 0 alone would keep key 0
+    big = 60.0
+    K = np.eye(3, 4, dtype=np.float32) * big
+    q0 = np.array([[1, 0, 0, 0]], dtype=np.float32) * big
+    a = math.log(0.6 / 0.4) * 2.0 / big ** 2  # logits of keys 1, 2 differ by ln(0.6/0.4): sqrt(d) = 2
+    q1 = np.array([[0, 1.0 + a / 2, 1.0 - a / 2, 0]], dtype=np.float32) * big
+    ph, tot, idx1, _, _ = O.step_layer([q0, q1, q1], [K[:0]] * 3, [K[:0]] * 3, [K] * 3, [K] * 3, 1)
+    assert abs(tot[0] - 1.0) < 1e-6 and abs(tot[1] - 1.2) < 1e-3 and abs(tot[2] - 0.8) < 1e-3
+    assert idx1.tolist() == [1] and O.top_r(ph[0], 1).tolist() == [0]
+    # identical heads: the layer's choice is each head's choice
+    phs, tots, idxs, _, _ = O.step_layer([Qs[0]] * 4, [Kc[0]] * 4, [Vc[0]] * 4, [Kk[0]] * 4, [Vk[0]] * 4, r)
+    assert idxs.tolist() == O.top_r(phs[0], r).tolist()
+    assert np.abs(tots - 4 * phs[0]).max() < 1e-13
+
+
+def pin_constant_budget_schedule(O):
+    # every step keeps min(k, candidates): C4's shape (131072 tokens, chunks of 4096, k = 1408)
+    rs = O.schedule(131072, 4096, 1408, constant_budget=True)
+    assert rs == [1408] * 32
+    keys = sum((rs[i - 1] if i else 0) + 4096 for i in range(32))
+    assert keys == 32 * 4096 + 31 * 1408          # = 174 720 keys scored per problem
+    assert O.schedule(1000, 300, 500, constant_budget=True) == [300, 500, 500, 500]
+    assert O.schedule(1000, 300, 5000, constant_budget=True) == [300, 600, 900, 1000]
+    assert O.schedule(131072, 4096, 1408)[-1] == 1408 and O.schedule(131072, 4096, 1408)[0] == 44
+
+
 ALL_PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_") and callable(v)]

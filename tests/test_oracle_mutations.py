@@ -14,6 +14,12 @@ SRC = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
                    "oracle", "finch_oracle.py")
 
 MUTATIONS = {
+    "layer_keeps_first_head_only": ("for s in per_head:\n        total = total + np.asarray(s, dtype=np.float64)",
+                                    "for s in per_head[:1]:\n        total = total + np.asarray(s, dtype=np.float64)"),
+    "layer_mean_of_maxima": ("    idx = top_r(total, r)\n    return (per_head", "    idx = top_r(per_head[0], r)\n    return (per_head"),
+    "layer_values_from_one_head": ("[gather_rows(idx, V_caches[h], V_chunks[h]) for h in range(H)])",
+                                   "[gather_rows(idx, V_caches[0], V_chunks[0]) for h in range(H)])"),
+    "constant_budget_ignored": ("k if constant_budget else (k * seen) // n_cont", "(k * seen) // n_cont"),
     "extra_keys_not_causal": ("s = S[row, :t + 1]", "s = S[row, :]"),
     "extra_keys_exclude_self": ("s = S[row, :t + 1]", "s = S[row, :max(t, 1)]"),
     "extra_rows_token_major": ("t = row % n_que\n        s = S[row", "t = row // group\n        s = S[row"),
@@ -56,8 +62,8 @@ MUTATIONS = {
     "bf16_low_half": ("(x.astype(np.uint32) << np.uint32(16))", "(x.astype(np.uint32))"),
     "values_from_key_rows": ("gather_rows(idx, K_cache, K_chunk), gather_rows(idx, V_cache, V_chunk)",
                              "gather_rows(idx, K_cache, K_chunk), gather_rows(idx, K_cache, K_chunk)"),
-    "schedule_ceiling": ("r = min(c + mi, (k * seen) // n_cont)", "r = min(c + mi, -((-k * seen) // n_cont))"),
-    "schedule_constant_budget": ("r = min(c + mi, (k * seen) // n_cont)", "r = min(c + mi, k)"),
+    "schedule_ceiling": ("k if constant_budget else (k * seen) // n_cont", "k if constant_budget else -((-k * seen) // n_cont)"),
+    "schedule_constant_budget": ("k if constant_budget else (k * seen) // n_cont", "k"),
     "cache_not_carried": ("Kc, Vc = Kn, Vn\n", "Kc, Vc = Kn[:0], Vn[:0]\n"),
     "scores_carried_not_rescored": ("q = Q[i] if isinstance(Q, (list, tuple)) else Q",
                                     "q = Q[0] if isinstance(Q, (list, tuple)) else Q"),
