@@ -96,6 +96,10 @@ def main() -> int:
                     help="rotate kept keys to their new slots while compacting (rotary pairing)")
     ap.add_argument("--order", default="ascending", choices=["ascending", "rank"],
                     help="slots of the kept rows in the new cache")
+    ap.add_argument("--layer-group", type=int, default=1,
+                    help="L > 1: one selection per run of L problems (the KV heads of a layer)")
+    ap.add_argument("--constant-budget", action="store_true",
+                    help="keep the whole budget k from the first step on")
     ap.add_argument("--exact-denominator", action="store_true",
                     help="softmax denominators include the prompt's own keys (random ones here)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -132,6 +136,8 @@ def main() -> int:
                         "interleaved": F.FINCH_ROPE_INTERLEAVED}[args.reposition],
                        {"ascending": F.FINCH_ORDER_ASCENDING, "rank": F.FINCH_ORDER_RANK}[args.order], 500000.0)
 
+    F.finch_set_option(fin.ctx, F.FINCH_OPT_LAYER_GROUP, args.layer_group)
+
     t_gen = time.perf_counter()
     probs = []
     for b, l, g in W.problems_of(w):
@@ -140,7 +146,8 @@ def main() -> int:
                           budget=w.requests[b].budget))
         if args.exact_denominator:
             probs[-1]["K_que"] = torch.randn(w.requests[b].n_que, w.head_dim, device=dev).to(p["K"].dtype)
-    loop = ChunkLoop(fin, probs, w.chunk, history=False, want_scores=False)
+    loop = ChunkLoop(fin, probs, w.chunk, history=False, want_scores=False,
+                     constant_budget=args.constant_budget)
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
     per_kernel_bytes, total_bytes, keys = algorithmic_bytes(w, loop)
@@ -217,7 +224,8 @@ def main() -> int:
                    "head_dim": w.head_dim, "group": w.group,
                    "path": args.path, "calls": "finch_step per chunk" if args.per_step else "finch_loop",
                    "reposition": args.reposition, "order": args.order,
-                   "exact_denominator": args.exact_denominator,
+                   "exact_denominator": args.exact_denominator, "layer_group": args.layer_group,
+                   "constant_budget": args.constant_budget,
                    "prompt_rows": [w.rows(r) for r in w.requests][:4],
                    "budget": [r.budget for r in w.requests][:4], "keys_scored": keys},
         "path": {"algorithmic_bytes": total_bytes, "achieved_GBps": path_gbps,

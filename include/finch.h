@@ -182,6 +182,12 @@ finch_status finch_loop(finch_ctx* ctx, const finch_problem* host_desc,
  * Writes ceil(n_cont/m) values; `r_len` is the capacity of r_out. */
 finch_status finch_schedule(int64_t n_cont, int32_t m, int64_t k, int32_t* r_out,
                             int32_t r_len);
+/* The same with a choice of rule: FINCH_SCHEDULE_PROPORTIONAL is the rule above;
+ * FINCH_SCHEDULE_CONSTANT keeps the whole budget from the start ("top-k under the
+ * budget" read literally): r_i = min(c_{i-1} + m_i, min(k, n_cont)). */
+typedef enum { FINCH_SCHEDULE_PROPORTIONAL = 0, FINCH_SCHEDULE_CONSTANT = 1 } finch_schedule_rule;
+finch_status finch_schedule_mode(int64_t n_cont, int32_t m, int64_t k, int32_t mode,
+                                 int32_t* r_out, int32_t r_len);
 
 /* Options.  FINCH_OPT_STEP_PATH picks how the stages are launched.  SEPARATE uses
  * one kernel per stage: row statistics, merge, per-key sums, top-r, compaction.
@@ -195,7 +201,17 @@ typedef enum {
   FINCH_OPT_STEP_PATH = 1,
   /* tuning: target number of keys one workgroup of the two-pass bf16 scoring
    * kernels streams (default 2400); a problem is cut into round((c+m)/value) slices */
-  FINCH_OPT_SLICE_KEYS = 3
+  FINCH_OPT_SLICE_KEYS = 3,
+  /* Layer-wise selection as the paper words it (Method: "Sum over heads", then ONE
+   * top-r per layer): value L > 1 makes every run of L consecutive problems of a
+   * batch one layer (its KV heads; same c, m and r, batch size a multiple of L, else
+   * FINCH_ERR_INVALID_ARG).  finch_topk, finch_step and finch_loop then add the
+   * run's score vectors head by head, select once on the sum and write the same
+   * indices to every problem of the run; each head compacts its own rows.  The
+   * per-problem scores stay as they are.  1 (default): one selection per problem.
+   * Runs are processed with one kernel per stage; FINCH_ORDER_RANK is refused
+   * (FINCH_ERR_UNSUPPORTED) while L > 1. */
+  FINCH_OPT_LAYER_GROUP = 4
 } finch_option;
 typedef enum { FINCH_PATH_AUTO = 0, FINCH_PATH_SEPARATE = 1, FINCH_PATH_OWNER = 3 } finch_path;
 finch_status finch_set_option(finch_ctx* ctx, int32_t option, int64_t value);

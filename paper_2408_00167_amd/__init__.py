@@ -28,7 +28,7 @@ FINCH_BF16 = 1
 
 EXPORTED_SYMBOLS = (
     "finch_create", "finch_destroy", "finch_workspace_size", "finch_score", "finch_topk",
-    "finch_compact", "finch_step", "finch_schedule", "finch_last_hip_error",
+    "finch_compact", "finch_step", "finch_schedule", "finch_schedule_mode", "finch_last_hip_error",
     "finch_status_string", "finch_version", "finch_profile", "finch_profile_read",
     "finch_set_option", "finch_set_reposition", "finch_prompt_lse", "finch_loop", "finch_loop_workspace_size",
 )
@@ -37,6 +37,8 @@ KERNEL_NAMES = ("rowstats", "lse", "colsum", "select", "gather", "owner", "promp
 
 FINCH_OPT_STEP_PATH = 1
 FINCH_OPT_SLICE_KEYS = 3
+FINCH_OPT_LAYER_GROUP = 4
+FINCH_SCHEDULE_PROPORTIONAL, FINCH_SCHEDULE_CONSTANT = 0, 1
 FINCH_PATH_AUTO = 0
 FINCH_PATH_SEPARATE = 1
 FINCH_PATH_OWNER = 3
@@ -95,6 +97,8 @@ def load_library() -> ctypes.CDLL:
         fn.restype = ctypes.c_int
     lib.finch_schedule.argtypes = [i64, i32, i64, P(i32), i32]
     lib.finch_schedule.restype = ctypes.c_int
+    lib.finch_schedule_mode.argtypes = [i64, i32, i64, i32, P(i32), i32]
+    lib.finch_schedule_mode.restype = ctypes.c_int
     lib.finch_last_hip_error.argtypes = [vp]
     lib.finch_last_hip_error.restype = i32
     lib.finch_status_string.argtypes = [ctypes.c_int]
@@ -177,10 +181,14 @@ def finch_step(ctx, host_desc, dev_desc_ptr, n, ws_ptr, ws_bytes, stream=0):
     _call("finch_step", ctx, host_desc, dev_desc_ptr, n, ws_ptr, ws_bytes, stream)
 
 
-def finch_schedule(n_cont: int, m: int, k: int) -> List[int]:
+def finch_schedule(n_cont: int, m: int, k: int, constant_budget: bool = False) -> List[int]:
     steps = max(0, -(-n_cont // m)) if m > 0 else 0
     buf = (ctypes.c_int32 * max(1, steps))()
-    _check(load_library().finch_schedule(n_cont, m, k, buf, steps), "finch_schedule")
+    if constant_budget:
+        _check(load_library().finch_schedule_mode(n_cont, m, k, FINCH_SCHEDULE_CONSTANT, buf, steps),
+               "finch_schedule_mode")
+    else:
+        _check(load_library().finch_schedule(n_cont, m, k, buf, steps), "finch_schedule")
     return list(buf[:steps])
 
 

@@ -24,6 +24,7 @@ struct finch_ctx {
   int step_path;         // FINCH_PATH_AUTO / _SEPARATE / _OWNER
   int slice_keys;        // target keys per workgroup slice of the bf16 scoring kernels
   finch_reposition repos;  // {OFF, ASCENDING}: plain copies
+  int layer_group;         // > 1: runs of that many problems share one selection
 };
 
 namespace {
@@ -44,7 +45,7 @@ struct Plan {
   int32_t own_row_chunk = 32;
   size_t own_lds = 0;
   size_t lds_bytes = 0;
-  size_t off_stats = 0, off_lse = 0, off_scores = 0, total = 0;
+  size_t off_stats = 0, off_lse = 0, off_scores = 0, off_layer = 0, total = 0;
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -120,6 +121,9 @@ finch_status make_plan(const finch_ctx* ctx, const finch_problem* hd, int32_t n_
   off = align_up(off + na * pl.rpad_max * sizeof(float), 256);
   pl.off_scores = off;
   off = align_up(off + na * pl.score_stride * sizeof(float), 256);
+  pl.off_layer = off;
+  if (ctx->layer_group > 1)
+    off = align_up(off + (na / ctx->layer_group + 1) * pl.score_stride * sizeof(float), 256);
   pl.total = off;
   return FINCH_OK;
 }
@@ -238,7 +242,8 @@ bool repositioning(const finch_ctx* ctx) {
 }
 
 bool owner_wanted(const finch_ctx* ctx, const Plan& pl, int32_t n) {
-  if (!pl.own_ok || n <= 0 || repositioning(ctx)) return false;
+  // a workgroup that owns one problem can neither re-position nor share a selection
+  if (!pl.own_ok || n <= 0 || repositioning(ctx) || ctx->layer_group > 1) return false;
   if (ctx->step_path == FINCH_PATH_OWNER) return true;
   if (ctx->step_path != FINCH_PATH_AUTO) return false;
   const int64_t cu = ctx->n_cu > 0 ? ctx->n_cu : 256;
@@ -284,11 +289,26 @@ finch_status run_score(finch_ctx* ctx, const LaunchParams& p, const Plan& pl, hi
   return FINCH_OK;
 }
 
-finch_status run_select(finch_ctx* ctx, const LaunchParams& p, hipStream_t s) {
+// Layer groups: the batch must be whole runs of problems with the same c, m and r.
+finch_status check_layer_runs(const finch_ctx* ctx, const finch_problem* hd, int32_t n) {
+  const int L = ctx->layer_group;
+  if (L <= 1) return FINCH_OK;
+  if (n % L != 0) return FINCH_ERR_INVALID_ARG;
+  for (int32_t i = 0; i < n; ++i) {
+    const finch_problem& a = hd[i - i % L];
+    if (hd[i].c != a.c || hd[i].m != a.m || hd[i].r != a.r) return FINCH_ERR_INVALID_ARG;
+  }
+  return FINCH_OK;
+}
+
+finch_status run_select(finch_ctx* ctx, const LaunchParams& p, const Plan& pl, void* ws, hipStream_t s) {
   hipError_t e;
   {
     ProfScope ps(ctx, FINCH_KERNEL_SELECT, s);
-    e = finch::launch_select(p, s);
+    e = ctx->layer_group > 1
+            ? finch::launch_select_layer(p, ctx->layer_group,
+                                         reinterpret_cast<float*>(static_cast<char*>(ws) + pl.off_layer), s)
+            : finch::launch_select(p, s);
   }
   return e == hipSuccess ? FINCH_OK : hip_fail(ctx, e);
 }
@@ -297,6 +317,8 @@ finch_status run_gather(finch_ctx* ctx, const LaunchParams& p, int r_max, hipStr
   hipError_t e;
   const bool rank = ctx->repos.order == FINCH_ORDER_RANK;
   if (rank && r_max > finch::kRankMaxRows) return FINCH_ERR_CAPACITY;
+  // rank-order slots come from each problem's own scores; a layer's heads must share slots
+  if (rank && ctx->layer_group > 1) return FINCH_ERR_UNSUPPORTED;
   {
     ProfScope ps(ctx, FINCH_KERNEL_GATHER, s);
     e = repositioning(ctx)
@@ -351,6 +373,7 @@ finch_status finch_create(const finch_config* cfg, finch_ctx** out) {
   ctx->n_cu = 0;
   ctx->step_path = FINCH_PATH_AUTO;
   ctx->slice_keys = finch::kDefaultSliceKeys;
+  ctx->layer_group = 1;
   ctx->repos.pairing = FINCH_ROPE_OFF;
   ctx->repos.order = FINCH_ORDER_ASCENDING;
   ctx->repos.base = 10000.0;
@@ -395,6 +418,10 @@ finch_status finch_set_option(finch_ctx* ctx, int32_t option, int64_t value) {
       if (value != FINCH_PATH_AUTO && value != FINCH_PATH_SEPARATE && value != FINCH_PATH_OWNER)
         return FINCH_ERR_INVALID_ARG;
       ctx->step_path = static_cast<int>(value);
+      return FINCH_OK;
+    case FINCH_OPT_LAYER_GROUP:
+      if (value < 1 || value > 4096) return FINCH_ERR_INVALID_ARG;
+      ctx->layer_group = static_cast<int>(value);
       return FINCH_OK;
     case FINCH_OPT_SLICE_KEYS:
       if (value < 256 || value > (1 << 24)) return FINCH_ERR_INVALID_ARG;
@@ -519,10 +546,11 @@ finch_status finch_topk(finch_ctx* ctx, const finch_problem* host_desc,
   Plan pl;
   if ((st = make_plan(ctx, host_desc, n, pl)) != FINCH_OK) return st;
   if ((st = validate(ctx, host_desc, n, kNeedScoresOut | kNeedIdx)) != FINCH_OK) return st;
+  if ((st = check_layer_runs(ctx, host_desc, n)) != FINCH_OK) return st;
   if ((st = check_workspace(pl, ws, ws_bytes)) != FINCH_OK) return st;
   if (n == 0 || pl.r_max == 0) return FINCH_OK;
   const LaunchParams p = make_params(ctx, dev_desc, n, pl, ws);
-  return run_select(ctx, p, static_cast<hipStream_t>(stream));
+  return run_select(ctx, p, pl, ws, static_cast<hipStream_t>(stream));
 }
 
 finch_status finch_compact(finch_ctx* ctx, const finch_problem* host_desc,
@@ -548,6 +576,7 @@ finch_status finch_step(finch_ctx* ctx, const finch_problem* host_desc,
   Plan pl;
   if ((st = make_plan(ctx, host_desc, n, pl)) != FINCH_OK) return st;
   if ((st = validate(ctx, host_desc, n, kNeedQK | kNeedIdx | kNeedGather)) != FINCH_OK) return st;
+  if ((st = check_layer_runs(ctx, host_desc, n)) != FINCH_OK) return st;
   if ((st = check_workspace(pl, ws, ws_bytes)) != FINCH_OK) return st;
   if (n == 0) return FINCH_OK;
   const LaunchParams p = make_params(ctx, dev_desc, n, pl, ws);
@@ -556,7 +585,7 @@ finch_status finch_step(finch_ctx* ctx, const finch_problem* host_desc,
   if (ctx->step_path == FINCH_PATH_OWNER && pl.tiles_max > 0) return FINCH_ERR_UNSUPPORTED;
   if ((st = run_score(ctx, p, pl, s)) != FINCH_OK) return st;
   if (pl.r_max == 0) return FINCH_OK;
-  if ((st = run_select(ctx, p, s)) != FINCH_OK) return st;
+  if ((st = run_select(ctx, p, pl, ws, s)) != FINCH_OK) return st;
   return run_gather(ctx, p, pl.r_max, s);
 }
 
@@ -610,6 +639,12 @@ finch_status finch_loop(finch_ctx* ctx, const finch_problem* host_desc, const fi
 }
 
 finch_status finch_schedule(int64_t n_cont, int32_t m, int64_t k, int32_t* r_out, int32_t r_len) {
+  return finch_schedule_mode(n_cont, m, k, FINCH_SCHEDULE_PROPORTIONAL, r_out, r_len);
+}
+
+finch_status finch_schedule_mode(int64_t n_cont, int32_t m, int64_t k, int32_t mode, int32_t* r_out,
+                                 int32_t r_len) {
+  if (mode != FINCH_SCHEDULE_PROPORTIONAL && mode != FINCH_SCHEDULE_CONSTANT) return FINCH_ERR_INVALID_ARG;
   if (n_cont < 0 || m < 1 || k < 0 || r_len < 0) return FINCH_ERR_INVALID_ARG;
   if (n_cont > (int64_t{1} << 40)) return FINCH_ERR_CAPACITY;
   const int64_t steps = (n_cont + m - 1) / m;
@@ -622,7 +657,7 @@ finch_status finch_schedule(int64_t n_cont, int32_t m, int64_t k, int32_t* r_out
     seen += mi;
     // floor(budget * seen / n_cont) without overflow: both factors are < 2^41
     const __int128 prod = static_cast<__int128>(budget) * seen;
-    int64_t r = static_cast<int64_t>(prod / n_cont);
+    int64_t r = mode == FINCH_SCHEDULE_CONSTANT ? budget : static_cast<int64_t>(prod / n_cont);
     if (r > kept + mi) r = kept + mi;
     if (r > INT32_MAX) return FINCH_ERR_CAPACITY;
     r_out[i] = static_cast<int32_t>(r);

@@ -58,6 +58,7 @@ hipError_t launch_rowstats_f32(int head_dim, const LaunchParams& p, size_t lds, 
 hipError_t launch_colsum_f32(int head_dim, const LaunchParams& p, size_t lds, hipStream_t s);
 hipError_t launch_lse(const LaunchParams& p, hipStream_t s);
 hipError_t launch_select(const LaunchParams& p, hipStream_t s);
+hipError_t launch_select_layer(const LaunchParams& p, int group, float* layer_scores, hipStream_t s);
 hipError_t launch_gather(const LaunchParams& p, int row_bytes, int r_max, hipStream_t s);
 size_t owner_lds_bytes(int head_dim, int row_chunk);
 hipError_t launch_prompt_lse(const LaunchParams& p, int head_dim, bool bf16, int rows_max, hipStream_t s);

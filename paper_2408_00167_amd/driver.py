@@ -32,10 +32,12 @@ class ChunkLoop:
     chunk: m, document rows per step.
     history: keep the scores and indices of every step (tests); otherwise one
         scores/idx buffer is reused by all steps.
+    constant_budget: keep the whole budget from the first step on instead of growing
+        r in proportion to the tokens seen.
     """
 
     def __init__(self, fin: Finch, problems: Sequence[Dict], chunk: int, history: bool = False,
-                 want_scores: bool = True):
+                 want_scores: bool = True, constant_budget: bool = False):
         self.fin = fin
         self.problems = list(problems)
         self.chunk = int(chunk)
@@ -47,7 +49,7 @@ class ChunkLoop:
         for pb in self.problems:
             n = int(pb["K"].shape[0])
             self.n_cont.append(n)
-            self.rs.append(finch_schedule(n, self.chunk, int(pb["budget"])))
+            self.rs.append(finch_schedule(n, self.chunk, int(pb["budget"]), constant_budget))
         self.n_steps = max((len(r) for r in self.rs), default=0)
         d = int(self.problems[0]["K"].shape[1]) if P else 0
         dtype = self.problems[0]["K"].dtype if P else torch.float32

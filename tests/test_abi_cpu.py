@@ -41,6 +41,7 @@ def test_schedule_matches_paper_rule_and_oracle():
                          (777, 100, 777), (65536, 2048, 2048), (3000, 7, 1), (40000, 2048, 1250),
                          (1 << 33, 1 << 20, 12345)]:
         assert F.finch_schedule(n_cont, m, k) == O.schedule(n_cont, m, k)
+        assert F.finch_schedule(n_cont, m, k, constant_budget=True) == O.schedule(n_cont, m, k, constant_budget=True)
     assert F.finch_schedule(0, 16, 4) == []
 
 
