@@ -191,7 +191,7 @@ finch_status finch_schedule_mode(int64_t n_cont, int32_t m, int64_t k, int32_t m
 
 /* Options.  FINCH_OPT_STEP_PATH picks how the stages are launched.  SEPARATE uses
  * one kernel per stage: row statistics, merge, per-key sums, top-r, compaction.
- * OWNER (bf16 only) gives every problem to one workgroup of 16 waves that runs all
+ * OWNER (bf16 only) gives every problem to one workgroup of 8 waves that runs all
  * stages of the step - or, in finch_loop, of all steps - back to back with nothing
  * exchanged between workgroups; batches it cannot run fail with
  * FINCH_ERR_UNSUPPORTED.  AUTO (default) takes OWNER when the batch has enough

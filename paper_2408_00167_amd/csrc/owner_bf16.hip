@@ -8,7 +8,7 @@
 // atomics on device memory and no waits: the row statistics are merged in LDS, the
 // scores a workgroup wrote are read back by itself (top-r), and so are the indices
 // (compaction).  The keys are read a second time right after the first pass, while
-// the memory-side cache still holds most of them.  Workgroups are 16 waves, one
+// the memory-side cache still holds most of them.  Workgroups are 8 waves (two per SIMD, up to 256 registers each), one
 // per CU; the batch should have about as many problems as the chip has CUs (or a
 // multiple), which the host checks before it picks this path.
 //
@@ -23,7 +23,7 @@ namespace finch {
 
 namespace {
 
-constexpr int kOwnThreads = kSelThreads;
+constexpr int kOwnThreads = 512;
 constexpr int kOwnWaves = kOwnThreads / 64;
 
 __device__ __forceinline__ int own_next_block(int* counter, int lane) {
@@ -125,41 +125,55 @@ __device__ __forceinline__ void own_step_body(const LaunchParams& prm, const fin
       // wave's first key block and moved (sum rescaled) only when a block's sum shows
       // that its logits lie far above it.
       bool seeded = false;
+      // statistics of one 32 x 32 logit block
+      auto tile_stats = [&](f32x16 a, int q, int kbase, bool ragged) {
+        if (ragged) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            if (kbase + acc_key(v, h) >= N) a[v] = -kInf;
+        }
+        float z = 0.f;
+        bool move = !seeded;
+        if (seeded) {
+          const float mu = (m_run[q] == -kInf) ? 0.f : m_run[q];
+#pragma unroll
+          for (int v = 0; v < 16; ++v) z += fast_exp2(__builtin_fmaf(a[v], sc, -mu));
+          move = __any(!(z <= 0x1p64f));
+        }
+        if (move) {
+          float bm = fmaxf(a[0], a[1]);
+#pragma unroll
+          for (int v = 2; v < 16; v += 2) bm = fmaxf(fmaxf(bm, a[v]), a[v + 1]);
+          const float mn = fmaxf(m_run[q], bm * sc);
+          z_run[q] = (mn == -kInf) ? 0.f : z_run[q] * fast_exp2(m_run[q] - mn);
+          m_run[q] = mn;
+          const float mu = (mn == -kInf) ? 0.f : mn;
+          z = 0.f;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) z += fast_exp2(__builtin_fmaf(a[v], sc, -mu));
+        }
+        z_run[q] += z;
+      };
+      // Row blocks go through in pairs, one pair behind: while the matrix pipe works
+      // on the logits of pair i, the vector units take the exponentials of pair i - 1.
       auto process = [&](const bf16x8(&kf)[D / 16], int blk) {
         const int kbase = blk << 5;
         const bool ragged = kbase + 32 > N;
+        f32x16 acc[QBT];
 #pragma unroll
-        for (int q = 0; q < QBT; ++q) {
-          if (q < QB) {
-            bf16x8 qf[D / 16];
-            load_q_frags<D>(lds_q, q, lane, qf);
-            f32x16 a = mfma_block<D>(kf, qf);
-            if (ragged) {
-#pragma unroll
-              for (int v = 0; v < 16; ++v)
-                if (kbase + acc_key(v, h) >= N) a[v] = -kInf;
+        for (int q = 0; q < QBT + 2; q += 2) {
+          if (q < QBT && q < QB) {
+            if (q + 1 < QB) {
+              mfma_block_pair_lds<D>(kf, lds_q, q, lane, acc[q], acc[q + 1]);
+            } else {
+              bf16x8 qf0[D / 16];
+              load_q_frags<D>(lds_q, q, lane, qf0);
+              acc[q] = mfma_block<D>(kf, qf0);
             }
-            float z = 0.f;
-            bool move = !seeded;
-            if (seeded) {
-              const float mu = (m_run[q] == -kInf) ? 0.f : m_run[q];
-#pragma unroll
-              for (int v = 0; v < 16; ++v) z += fast_exp2(__builtin_fmaf(a[v], sc, -mu));
-              move = __any(!(z <= 0x1p64f));
-            }
-            if (move) {
-              float bm = fmaxf(a[0], a[1]);
-#pragma unroll
-              for (int v = 2; v < 16; v += 2) bm = fmaxf(fmaxf(bm, a[v]), a[v + 1]);
-              const float mn = fmaxf(m_run[q], bm * sc);
-              z_run[q] = (mn == -kInf) ? 0.f : z_run[q] * fast_exp2(m_run[q] - mn);
-              m_run[q] = mn;
-              const float mu = (mn == -kInf) ? 0.f : mn;
-              z = 0.f;
-#pragma unroll
-              for (int v = 0; v < 16; ++v) z += fast_exp2(__builtin_fmaf(a[v], sc, -mu));
-            }
-            z_run[q] += z;
+          }
+          if (q >= 2 && q - 2 < QB) {
+            tile_stats(acc[q - 2], q - 2, kbase, ragged);
+            if (q - 1 < QB) tile_stats(acc[q - 1], q - 1, kbase, ragged);
           }
         }
         seeded = true;
@@ -215,13 +229,28 @@ __device__ __forceinline__ void own_step_body(const LaunchParams& prm, const fin
         float u[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) u[v] = 0.f;
-        for (int q = 0; q < QB; ++q) {
-          bf16x8 qf[D / 16];
-          load_q_frags<D>(lds_q, q, lane, qf);
-          const f32x16 a = mfma_block<D>(kf, qf);
+        auto tile_sums = [&](const f32x16& a, int q) {
           const float L = lds_lse[q * 32 + t];
 #pragma unroll
           for (int v = 0; v < 16; ++v) u[v] += fast_exp2(__builtin_fmaf(a[v], sc, -L));
+        };
+        // pairs of row blocks, the vector work one pair behind the matrix work
+        f32x16 acc[QBT];
+#pragma unroll
+        for (int q = 0; q < QBT + 2; q += 2) {
+          if (q < QBT && q < QB) {
+            if (q + 1 < QB) {
+              mfma_block_pair_lds<D>(kf, lds_q, q, lane, acc[q], acc[q + 1]);
+            } else {
+              bf16x8 qf0[D / 16];
+              load_q_frags<D>(lds_q, q, lane, qf0);
+              acc[q] = mfma_block<D>(kf, qf0);
+            }
+          }
+          if (q >= 2 && q - 2 < QB) {
+            tile_sums(acc[q - 2], q - 2);
+            if (q - 1 < QB) tile_sums(acc[q - 1], q - 1);
+          }
         }
         const float tot = fold16_over32(u, t);
         const int key = kbase + acc_key(t >> 1, h);
@@ -267,8 +296,8 @@ __device__ __forceinline__ void own_step_body(const LaunchParams& prm, const fin
       lidx = reinterpret_cast<int*>(sel + used);
       used += static_cast<size_t>(r) * 4;
     }
-    if (N <= kSelThreads * kSelRegKeys) {
-      select_regs(dst, N, r, gidx, lidx, fl, tid, lane, wave);
+    if (N <= kOwnThreads * kSelRegKeys) {
+      select_regs<kOwnThreads>(dst, N, r, gidx, lidx, fl, tid, lane, wave);
     } else {
       unsigned* lkeys = nullptr;
       if (used + static_cast<size_t>(N) * 4 <= sel_bytes) {
@@ -276,7 +305,7 @@ __device__ __forceinline__ void own_step_body(const LaunchParams& prm, const fin
         for (int i = tid; i < N; i += kOwnThreads) lkeys[i] = order_key(dst[i]);
       }
       __syncthreads();
-      select_generic(lkeys, dst, N, r, gidx, lidx, fl, tid, lane, wave);
+      select_generic<kOwnThreads>(lkeys, dst, N, r, gidx, lidx, fl, tid, lane, wave);
     }
     __syncthreads();  // idx (LDS and memory) complete
   }

@@ -160,6 +160,54 @@ __device__ __forceinline__ f32x16 mfma_block(const bf16x8 (&kf)[D / 16], const b
   return a;
 }
 
+// Two 32x32 logit blocks of the same 32 keys against two blocks of 32 prompt rows,
+// as two independent accumulation chains issued alternately (a chain's next
+// instruction needs its previous result; two chains keep the matrix pipe fed).
+template <int D>
+__device__ __forceinline__ void mfma_block_pair(const bf16x8 (&kf)[D / 16], const bf16x8 (&qf0)[D / 16],
+                                                const bf16x8 (&qf1)[D / 16], f32x16& a0, f32x16& a1) {
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  a0 = zero;
+  a1 = zero;
+#pragma unroll
+  for (int s = 0; s < D / 16; ++s) {
+    a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf0[s], a0, 0, 0, 0);
+    a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf1[s], a1, 0, 0, 0);
+  }
+}
+
+// The same with the prompt rows read from LDS inside the chain, one k-step ahead of
+// the matrix instructions that use them (two 16-byte reads in flight while two
+// matrix instructions run), so that the LDS latency is hidden without holding all
+// sixteen operands in registers.  Row blocks qb and qb + 1.
+template <int D>
+__device__ __forceinline__ void mfma_block_pair_lds(const bf16x8 (&kf)[D / 16], const char* lds_q, int qb,
+                                                    int lane, f32x16& a0, f32x16& a1) {
+  constexpr int kStride = D * 2 + 16;
+  const char* r0 = lds_q + (qb * 32 + (lane & 31)) * kStride + 16 * (lane >> 5);
+  const char* r1 = r0 + 32 * kStride;
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  a0 = zero;
+  a1 = zero;
+  bf16x8 c0 = *reinterpret_cast<const bf16x8*>(r0);
+  bf16x8 c1 = *reinterpret_cast<const bf16x8*>(r1);
+#pragma unroll
+  for (int s = 0; s < D / 16; ++s) {
+    bf16x8 n0 = c0, n1 = c1;
+    if (s + 1 < D / 16) {
+      n0 = *reinterpret_cast<const bf16x8*>(r0 + 32 * (s + 1));
+      n1 = *reinterpret_cast<const bf16x8*>(r1 + 32 * (s + 1));
+    }
+    a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], c0, a0, 0, 0, 0);
+    a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], c1, a1, 0, 0, 0);
+    // keep this order in the schedule: two LDS reads, then two matrix instructions
+    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+    c0 = n0;
+    c1 = n1;
+  }
+}
+
 // Sum each of 16 per-lane values over the 32 lanes of a lane-half.  On return the
 // lane with in-half index t holds the total of value index t >> 1.  Fixed order.
 __device__ __forceinline__ float fold16_over32(const float (&u)[16], int t) {

@@ -1,5 +1,5 @@
-// Exact top-r of the per-key scores of one problem by one workgroup of 1024
-// threads (Method: t = top-r(A_agg, r)): ties to the lower index, output in
+// Exact top-r of the per-key scores of one problem by one workgroup of NT = 512 or
+// 1024 threads (Method: t = top-r(A_agg, r)): ties to the lower index, output in
 // ascending index order.  Shared by the selection kernel and the
 // one-workgroup-per-problem step kernel.
 //
@@ -13,8 +13,8 @@
 
 namespace finch {
 
-constexpr int kSelThreads = 1024;
-constexpr int kSelWaves = kSelThreads / 64;
+constexpr int kSelThreads = 1024;          // threads of the selection kernel
+constexpr int kSelMaxWaves = 16;           // most waves of any workgroup that selects
 // select_regs keeps up to this many candidates per thread in registers
 constexpr int kSelRegKeys = 8;
 
@@ -26,7 +26,7 @@ __device__ __forceinline__ unsigned order_key(float f) {
 
 struct SelLds {  // LDS scratch of a selection
   int hist[4][256];
-  int wave_tot[2][kSelWaves];
+  int wave_tot[2][kSelMaxWaves];
   int digit[4], remaining[4];
 };
 
@@ -65,6 +65,7 @@ __device__ __forceinline__ void sel_pick_digit(const int* hist, int remaining, i
 
 // Exclusive rank of `flag` among the workgroup's threads in thread order, and the
 // total.  Two barriers; every thread must call it.
+template <int NT>
 __device__ __forceinline__ int sel_block_rank(bool flag, int* wave_tot, int lane, int wave, int& total) {
   const unsigned long long b = __ballot(flag);
   const int below = __popcll(b & ((1ull << lane) - 1ull));
@@ -72,7 +73,7 @@ __device__ __forceinline__ int sel_block_rank(bool flag, int* wave_tot, int lane
   __syncthreads();
   int base = 0, tot = 0;
 #pragma unroll
-  for (int w = 0; w < kSelWaves; ++w) {
+  for (int w = 0; w < NT / 64; ++w) {
     const int x = wave_tot[w];
     if (w < wave) base += x;
     tot += x;
@@ -84,6 +85,7 @@ __device__ __forceinline__ int sel_block_rank(bool flag, int* wave_tot, int lane
 
 // Exclusive prefix sum of `v` over the workgroup's threads in thread order.  One
 // barrier; `wave_tot` must not be reused before another barrier.
+template <int NT>
 __device__ __forceinline__ int sel_block_scan(int v, int* wave_tot, int lane, int wave) {
   int incl = v;
 #pragma unroll
@@ -95,7 +97,7 @@ __device__ __forceinline__ int sel_block_scan(int v, int* wave_tot, int lane, in
   __syncthreads();
   int base = 0;
 #pragma unroll
-  for (int w = 0; w < kSelWaves; ++w) {
+  for (int w = 0; w < NT / 64; ++w) {
     const int x = wave_tot[w];
     if (w < wave) base += x;
   }
@@ -105,6 +107,7 @@ __device__ __forceinline__ int sel_block_scan(int v, int* wave_tot, int lane, in
 // Any N.  `keys` is LDS (order keys staged there) or nullptr (scores re-read from
 // memory each round).  Writes idx to `gidx` and, if `lidx` is not null, also to
 // LDS.  0 < r < N.  Whole workgroup; starts and ends without a barrier.
+template <int NT>
 __device__ __forceinline__ void select_generic(const unsigned* keys, const FINCH_GLOBAL float* gscores,
                                                int N, int r, FINCH_GLOBAL int* gidx, int* lidx, SelLds* f,
                                                int tid, int lane, int wave) {
@@ -115,7 +118,7 @@ __device__ __forceinline__ void select_generic(const unsigned* keys, const FINCH
   for (int shift = 24; shift >= 0; shift -= 8) {
     if (tid < 256) hist[tid] = 0;
     __syncthreads();
-    for (int i = tid; i < N; i += kSelThreads) {
+    for (int i = tid; i < N; i += NT) {
       const unsigned key = key_at(i);
       if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
     }
@@ -130,16 +133,16 @@ __device__ __forceinline__ void select_generic(const unsigned* keys, const FINCH
   const unsigned T = prefix;
   const int need_eq = remaining;  // candidates equal to T that are kept (>= 1)
   int carry_eq = 0, carry_keep = 0;
-  for (int base = 0; base < N; base += kSelThreads) {
+  for (int base = 0; base < N; base += NT) {
     const int i = base + tid;
     const bool valid = i < N;
     const unsigned key = valid ? key_at(i) : 0u;
     const bool gt = valid && key > T;
     const bool eq = valid && key == T;
     int tot_eq, tot_keep;
-    const int eq_rank = carry_eq + sel_block_rank(eq, f->wave_tot[0], lane, wave, tot_eq);
+    const int eq_rank = carry_eq + sel_block_rank<NT>(eq, f->wave_tot[0], lane, wave, tot_eq);
     const bool keep = gt || (eq && eq_rank < need_eq);
-    const int pos = carry_keep + sel_block_rank(keep, f->wave_tot[0], lane, wave, tot_keep);
+    const int pos = carry_keep + sel_block_rank<NT>(keep, f->wave_tot[0], lane, wave, tot_keep);
     if (keep) {
       gidx[pos] = i;
       if (lidx) lidx[pos] = i;
@@ -149,22 +152,23 @@ __device__ __forceinline__ void select_generic(const unsigned* keys, const FINCH
   }
 }
 
-// N <= kSelThreads * kSelRegKeys: thread t owns the candidates [t*K, t*K+K),
-// K = ceil(N / 1024), and keeps their order keys in registers, so the four radix
+// N <= NT * kSelRegKeys: thread t owns the candidates [t*K, t*K+K),
+// K = ceil(N / NT), and keeps their order keys in registers, so the four radix
 // rounds touch LDS only for the histograms (lanes of a wave that hit the same bin
 // as the wave's first active lane are counted with one atomic) and the ordered
 // output needs two workgroup scans.  0 < r < N.  Whole workgroup; starts with a
 // barrier of its own and ends without one.
+template <int NT>
 __device__ __forceinline__ void select_regs(const FINCH_GLOBAL float* gscores, int N, int r,
                                             FINCH_GLOBAL int* gidx, int* lidx, SelLds* f, int tid,
                                             int lane, int wave) {
-  const int K = (N + kSelThreads - 1) / kSelThreads;
+  const int K = (N + NT - 1) / NT;
   const int i0 = tid * K;
   const int nk = max(0, min(K, N - i0));  // candidates of this thread
   unsigned key[kSelRegKeys];
 #pragma unroll
   for (int k = 0; k < kSelRegKeys; ++k) key[k] = k < nk ? order_key(gscores[i0 + k]) : 0u;
-  (&f->hist[0][0])[tid] = 0;  // 4 * 256 bins, one per thread
+  for (int i = tid; i < 4 * 256; i += NT) (&f->hist[0][0])[i] = 0;
   __syncthreads();
   unsigned prefix = 0, mask = 0;
   int remaining = r;
@@ -197,7 +201,7 @@ __device__ __forceinline__ void select_regs(const FINCH_GLOBAL float* gscores, i
   int c_eq = 0;
 #pragma unroll
   for (int k = 0; k < kSelRegKeys; ++k) c_eq += (k < nk && key[k] == T) ? 1 : 0;
-  int eq_rank = sel_block_scan(c_eq, f->wave_tot[0], lane, wave);
+  int eq_rank = sel_block_scan<NT>(c_eq, f->wave_tot[0], lane, wave);
   unsigned keep_bits = 0;
   int c_keep = 0;
 #pragma unroll
@@ -211,7 +215,7 @@ __device__ __forceinline__ void select_regs(const FINCH_GLOBAL float* gscores, i
       }
     }
   }
-  int pos = sel_block_scan(c_keep, f->wave_tot[1], lane, wave);
+  int pos = sel_block_scan<NT>(c_keep, f->wave_tot[1], lane, wave);
 #pragma unroll
   for (int k = 0; k < kSelRegKeys; ++k) {
     if (keep_bits & (1u << k)) {
