@@ -1,7 +1,7 @@
 // Selection kernel: exact top-r of the per-key scores of one problem (Method:
 // t = top-r(A_agg, r)), ties to the lower index, output in ascending index order.
 //
-// One workgroup per problem; the algorithm is in select_common.h.  Up to 8192
+// One workgroup per problem; the algorithm is in select_common.h.  Up to 16384
 // candidates are held in registers; larger problems re-read their scores (L2) in
 // every round.
 #include "select_common.h"

@@ -16,7 +16,7 @@ namespace finch {
 constexpr int kSelThreads = 1024;          // threads of the selection kernel
 constexpr int kSelMaxWaves = 16;           // most waves of any workgroup that selects
 // select_regs keeps up to this many candidates per thread in registers
-constexpr int kSelRegKeys = 8;
+constexpr int kSelRegKeys = 16;
 
 // Monotone map float -> uint32 (larger float <=> larger key); -0 counts as +0.
 __device__ __forceinline__ unsigned order_key(float f) {

@@ -17,7 +17,7 @@ LAYERS = [
     dict(n_que=16, c=64, m=0, r=10),
     dict(n_que=16, c=100, m=156, r=0),
     dict(n_que=16, c=100, m=156, r=256),      # keep everything
-    dict(n_que=3, c=0, m=9000, r=700),        # more candidates than the register select holds
+    dict(n_que=3, c=0, m=17000, r=700),       # more candidates than the register select holds
 ]
 
 

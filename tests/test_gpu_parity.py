@@ -71,7 +71,8 @@ def test_both_step_paths(d, group, path):
     fin.set_step_path(PATHS[path])
     cap = 512 // group
     specs = [dict(s, n_que=min(s["n_que"], cap)) for s in RAGGED_SPECS]
-    specs += [dict(n_que=cap, c=1364, m=4096, r=1408), dict(n_que=max(1, cap // 3), c=5, m=130, r=64)]
+    specs += [dict(n_que=cap, c=1364, m=4096, r=1408), dict(n_que=max(1, cap // 3), c=5, m=130, r=64),
+              dict(n_que=2, c=100, m=9000, r=900)]   # more candidates than a workgroup's registers hold
     batch, ts = H.single_step_case(fin, specs, torch.bfloat16, d, group, seed=300 + d + group)
     fin.step(batch)
     st = H.validate_single_step(ts, f"{path} d={d} G={group}")
