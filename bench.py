@@ -33,7 +33,7 @@ MEASURED_TRAFFIC = {"C4": {
     "colsum": 2.0 * 159570.6 * 1024 + 5804.0 * 1024,
     "select": 2.0 * 2520.6 * 1024 + 728.0 * 1024,
     "gather": 2.0 * 47121.4 * 1024 + 92928.0 * 1024,
-    "owner": 2.0 * 12845285.2 * 1024 + 4118656.1 * 1024,   # one launch = the whole loop
+    "owner": 2.0 * 11168763.7 * 1024 + 3149952.0 * 1024,   # one launch = the whole loop
 }}
 
 
