@@ -135,8 +135,8 @@ finch_status finch_compact(finch_ctx* ctx, const finch_problem* host_desc,
  * and at most 32768 kept rows per problem, else FINCH_ERR_CAPACITY).  Rotation is
  * computed in fp32 (angles reduced in fp64); bf16 results are rounded to nearest
  * even; a shift of 0 leaves the key bit-identical.  NULL, or {OFF, ASCENDING},
- * restores the plain copy.  While re-positioning is on, batches run with one kernel
- * per stage (FINCH_PATH_OWNER is refused with FINCH_ERR_UNSUPPORTED). */
+ * restores the plain copy.  With FINCH_ORDER_RANK batches run with one kernel per
+ * stage (FINCH_PATH_OWNER is refused with FINCH_ERR_UNSUPPORTED). */
 typedef enum { FINCH_ROPE_OFF = 0, FINCH_ROPE_HALF = 1, FINCH_ROPE_INTERLEAVED = 2 } finch_rope_pairing;
 typedef enum { FINCH_ORDER_ASCENDING = 0, FINCH_ORDER_RANK = 1 } finch_order;
 typedef struct {

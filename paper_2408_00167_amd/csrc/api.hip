@@ -206,6 +206,8 @@ LaunchParams make_params(const finch_ctx* ctx, const finch_problem* dd, int32_t 
   p.lse = reinterpret_cast<float*>(base + pl.off_lse);
   p.ws_scores = reinterpret_cast<float*>(base + pl.off_scores);
   p.lds_bytes = static_cast<uint32_t>(pl.lds_bytes);
+  p.rope_pairing = ctx->repos.pairing;
+  p.rope_log2_base = std::log2(ctx->repos.base);
   return p;
 }
 
@@ -242,8 +244,10 @@ bool repositioning(const finch_ctx* ctx) {
 }
 
 bool owner_wanted(const finch_ctx* ctx, const Plan& pl, int32_t n) {
-  // a workgroup that owns one problem can neither re-position nor share a selection
-  if (!pl.own_ok || n <= 0 || repositioning(ctx) || ctx->layer_group > 1) return false;
+  // a workgroup that owns one problem re-positions only to ascending slots and cannot
+  // share a selection with other problems
+  if (!pl.own_ok || n <= 0 || ctx->repos.order != FINCH_ORDER_ASCENDING || ctx->layer_group > 1)
+    return false;
   if (ctx->step_path == FINCH_PATH_OWNER) return true;
   if (ctx->step_path != FINCH_PATH_AUTO) return false;
   const int64_t cu = ctx->n_cu > 0 ? ctx->n_cu : 256;

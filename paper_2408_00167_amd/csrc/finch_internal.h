@@ -48,6 +48,9 @@ struct LaunchParams {
   float* lse;                  // [P][rpad_max] log2-domain log-sum-exp per prompt row
   float* ws_scores;            // [P][score_stride] used when desc.scores == NULL
   uint32_t lds_bytes;          // dynamic LDS of the launch
+  // re-positioning inside the one-workgroup-per-problem kernels (ascending slots)
+  int32_t rope_pairing;        // FINCH_ROPE_OFF / _HALF / _INTERLEAVED
+  double rope_log2_base;       // log2 of the rotary base
 };
 
 // Launchers; each returns hipGetLastError() after the launch.

@@ -16,6 +16,7 @@
 // assignment rules) follows the two-pass kernels: MFMA 32x32x16 bf16 with one
 // prompt row per lane, log2-domain softmax, pass 1 with a fixed assignment of key
 // blocks to waves, pass 2 with key blocks handed out by an LDS counter.
+#include "reposition_common.h"
 #include "score_common.h"
 #include "select_common.h"
 
@@ -70,6 +71,56 @@ __device__ __forceinline__ void own_gather(const finch_problem& pb, int N, int r
   }
 }
 
+// The same with the kept keys re-positioned to their (ascending) slots: row t is
+// turned by t - idx[t] positions while it is copied.  A thread owns two pieces of
+// a row, d/2 channels apart, i.e. both partners of its channel pairs.
+template <int SEGS>
+__device__ __forceinline__ void own_gather_rot(const finch_problem& pb, int N, int r, const int* lidx,
+                                               const FINCH_GLOBAL int* gidx, bool identity, int pairing,
+                                               double log2_base, int tid) {
+  constexpr int kHalf = SEGS / 2, E = 8;
+  const FINCH_GLOBAL u32x4* kc = as_global<u32x4>(pb.k_cache);
+  const FINCH_GLOBAL u32x4* kk = as_global<u32x4>(pb.k_chunk);
+  const FINCH_GLOBAL u32x4* vc = as_global<u32x4>(pb.v_cache);
+  const FINCH_GLOBAL u32x4* vk = as_global<u32x4>(pb.v_chunk);
+  FINCH_GLOBAL u32x4* ko = as_global_mut<u32x4>(pb.k_out);
+  FINCH_GLOBAL u32x4* vo = as_global_mut<u32x4>(pb.v_out);
+  constexpr int kRowsPerIter = kOwnThreads / kHalf;
+  constexpr int kUnroll = 4;
+  const int seg = tid % kHalf, sub = tid / kHalf;
+  double th[E];
+  pair_thetas<E, kHalf>(pairing, seg, log2_base, th);
+  for (int row0 = 0; row0 < r; row0 += kRowsPerIter * kUnroll) {
+    u32x4 ka[kUnroll], kb[kUnroll], va[kUnroll], vb[kUnroll];
+    int shift[kUnroll];
+#pragma unroll
+    for (int it = 0; it < kUnroll; ++it) {
+      const int t = min(row0 + it * kRowsPerIter + sub, r - 1);
+      int j = identity ? t : (lidx ? lidx[t] : gidx[t]);
+      j = min(max(j, 0), N - 1);
+      shift[it] = t - j;
+      const bool cached = j < pb.c;
+      const size_t off = static_cast<size_t>(cached ? j : j - pb.c) * SEGS + seg;
+      ka[it] = (cached ? kc : kk)[off];
+      kb[it] = (cached ? kc : kk)[off + kHalf];
+      va[it] = (cached ? vc : vk)[off];
+      vb[it] = (cached ? vc : vk)[off + kHalf];
+    }
+#pragma unroll
+    for (int it = 0; it < kUnroll; ++it) {
+      const int t = row0 + it * kRowsPerIter + sub;
+      if (t < r) {
+        if (shift[it] != 0) rotate_pieces<E>(pairing, th, shift[it], ka[it], kb[it]);
+        const size_t o = static_cast<size_t>(t) * SEGS + seg;
+        ko[o] = ka[it];
+        ko[o + kHalf] = kb[it];
+        vo[o] = va[it];
+        vo[o + kHalf] = vb[it];
+      }
+    }
+  }
+}
+
 }  // namespace
 
 // One step of one problem by the whole workgroup.  QBT = row blocks (of 32 prompt
@@ -80,7 +131,7 @@ __device__ __forceinline__ void own_gather(const finch_problem& pb, int N, int r
 // count mean the same rows and the copy is skipped.  Ends with every thread past
 // its last access to LDS only after the next barrier: callers that go on to
 // another step must put a barrier in between.
-template <int D, int QBT>
+template <int D, int QBT, bool ROT>
 __device__ __forceinline__ void own_step_body(const LaunchParams& prm, const finch_problem& pb, int slot,
                                               int stages, char* smem, const void*& staged_q,
                                               int& staged_rows) {
@@ -311,18 +362,23 @@ __device__ __forceinline__ void own_step_body(const LaunchParams& prm, const fin
   }
 
   // ---- compaction
-  own_gather<D / 8>(pb, N, r, lidx, gidx, identity, tid);
+  if (ROT) {
+    own_gather_rot<D / 8>(pb, N, r, lidx, gidx, identity, prm.rope_pairing, prm.rope_log2_base, tid);
+  } else {
+    own_gather<D / 8>(pb, N, r, lidx, gidx, identity, tid);
+  }
 }
 
 // One launch = one step of every problem of a batch; workgroup b owns problem b.
-template <int D, int QBT>
+// ROT: the compaction re-positions the kept keys (prm.rope_pairing, ascending slots).
+template <int D, int QBT, bool ROT>
 __global__ __launch_bounds__(kOwnThreads) void owner_step_bf16(LaunchParams prm, int stages) {
   extern __shared__ __align__(16) char smem[];
   const int p = blockIdx.x;
   const finch_problem pb = prm.probs[p];
   const void* staged_q = nullptr;
   int staged_rows = 0;
-  own_step_body<D, QBT>(prm, pb, p, stages, smem, staged_q, staged_rows);
+  own_step_body<D, QBT, ROT>(prm, pb, p, stages, smem, staged_q, staged_rows);
 }
 
 // One launch = the whole chunk loop (Method: Document Segmentation): workgroup b
@@ -330,7 +386,7 @@ __global__ __launch_bounds__(kOwnThreads) void owner_step_bf16(LaunchParams prm,
 // are prm.probs[step_first[s] + slot] for slot < step_first[s+1] - step_first[s].
 // Slots do not depend on each other, so workgroups drift apart and the copy-bound
 // and arithmetic-bound stages of different problems overlap.
-template <int D, int QBT>
+template <int D, int QBT, bool ROT>
 __global__ __launch_bounds__(kOwnThreads) void owner_loop_bf16(LaunchParams prm, const int* step_first,
                                                                int n_steps) {
   extern __shared__ __align__(16) char smem[];
@@ -341,7 +397,7 @@ __global__ __launch_bounds__(kOwnThreads) void owner_loop_bf16(LaunchParams prm,
     const int first = step_first[s];
     if (slot >= step_first[s + 1] - first) break;  // slots are filled from the front
     const finch_problem pb = prm.probs[first + slot];
-    own_step_body<D, QBT>(prm, pb, slot, /*stages=*/1, smem, staged_q, staged_rows);
+    own_step_body<D, QBT, ROT>(prm, pb, slot, /*stages=*/1, smem, staged_q, staged_rows);
     // the rows this step wrote are the next step's cache: complete before it reads
     __syncthreads();
   }
@@ -357,47 +413,33 @@ int own_qbt(int row_chunk) {
   return 0;
 }
 
-template <int D>
-const void* owner_ptr(int qbt) {
-  switch (qbt) {
-    case 2: return reinterpret_cast<const void*>(&owner_step_bf16<D, 2>);
-    case 4: return reinterpret_cast<const void*>(&owner_step_bf16<D, 4>);
-    case 6: return reinterpret_cast<const void*>(&owner_step_bf16<D, 6>);
-    default: return reinterpret_cast<const void*>(&owner_step_bf16<D, 8>);
+// Calls f(kernel) for the instantiation that matches (head_dim, qbt, rot); `loop`
+// picks the whole-loop kernel.  Returns false for a combination that is not built.
+template <typename F>
+bool with_step_kernel(int head_dim, int qbt, bool rot, F f) {
+#define FINCH_OWN_CASE(DD, QQ)                                           \
+  if (head_dim == DD && qbt == QQ) {                                     \
+    if (rot) f(&owner_step_bf16<DD, QQ, true>);                          \
+    else f(&owner_step_bf16<DD, QQ, false>);                             \
+    return true;                                                         \
   }
+  FINCH_OWN_CASE(128, 2) FINCH_OWN_CASE(128, 4) FINCH_OWN_CASE(128, 6) FINCH_OWN_CASE(128, 8)
+  FINCH_OWN_CASE(64, 2) FINCH_OWN_CASE(64, 4) FINCH_OWN_CASE(64, 6) FINCH_OWN_CASE(64, 8)
+#undef FINCH_OWN_CASE
+  return false;
 }
-
-template <int D>
-const void* owner_loop_ptr(int qbt) {
-  switch (qbt) {
-    case 2: return reinterpret_cast<const void*>(&owner_loop_bf16<D, 2>);
-    case 4: return reinterpret_cast<const void*>(&owner_loop_bf16<D, 4>);
-    case 6: return reinterpret_cast<const void*>(&owner_loop_bf16<D, 6>);
-    default: return reinterpret_cast<const void*>(&owner_loop_bf16<D, 8>);
+template <typename F>
+bool with_loop_kernel(int head_dim, int qbt, bool rot, F f) {
+#define FINCH_OWN_CASE(DD, QQ)                                           \
+  if (head_dim == DD && qbt == QQ) {                                     \
+    if (rot) f(&owner_loop_bf16<DD, QQ, true>);                          \
+    else f(&owner_loop_bf16<DD, QQ, false>);                             \
+    return true;                                                         \
   }
-}
-
-template <int D>
-void launch_owner_loop_d(int qbt, dim3 grid, size_t lds, hipStream_t s, const LaunchParams& p,
-                         const int* step_first, int n_steps) {
-  const dim3 block(kOwnThreads);
-  switch (qbt) {
-    case 2: hipLaunchKernelGGL((owner_loop_bf16<D, 2>), grid, block, lds, s, p, step_first, n_steps); break;
-    case 4: hipLaunchKernelGGL((owner_loop_bf16<D, 4>), grid, block, lds, s, p, step_first, n_steps); break;
-    case 6: hipLaunchKernelGGL((owner_loop_bf16<D, 6>), grid, block, lds, s, p, step_first, n_steps); break;
-    default: hipLaunchKernelGGL((owner_loop_bf16<D, 8>), grid, block, lds, s, p, step_first, n_steps); break;
-  }
-}
-
-template <int D>
-void launch_owner_d(int qbt, dim3 grid, size_t lds, hipStream_t s, const LaunchParams& p, int stages) {
-  const dim3 block(kOwnThreads);
-  switch (qbt) {
-    case 2: hipLaunchKernelGGL((owner_step_bf16<D, 2>), grid, block, lds, s, p, stages); break;
-    case 4: hipLaunchKernelGGL((owner_step_bf16<D, 4>), grid, block, lds, s, p, stages); break;
-    case 6: hipLaunchKernelGGL((owner_step_bf16<D, 6>), grid, block, lds, s, p, stages); break;
-    default: hipLaunchKernelGGL((owner_step_bf16<D, 8>), grid, block, lds, s, p, stages); break;
-  }
+  FINCH_OWN_CASE(128, 2) FINCH_OWN_CASE(128, 4) FINCH_OWN_CASE(128, 6) FINCH_OWN_CASE(128, 8)
+  FINCH_OWN_CASE(64, 2) FINCH_OWN_CASE(64, 4) FINCH_OWN_CASE(64, 6) FINCH_OWN_CASE(64, 8)
+#undef FINCH_OWN_CASE
+  return false;
 }
 
 }  // namespace
@@ -416,15 +458,11 @@ size_t owner_lds_bytes(int head_dim, int row_chunk) {
 // p.row_chunk and p.lds_bytes must describe this kernel's layout (owner_lds_bytes).
 hipError_t launch_owner_bf16(int head_dim, const LaunchParams& p, int stages, hipStream_t s) {
   if (p.n_problems <= 0) return hipSuccess;
-  const int qbt = own_qbt(p.row_chunk);
-  if (qbt == 0) return hipErrorInvalidValue;
-  const dim3 grid(static_cast<unsigned>(p.n_problems));
-  if (head_dim == 128) {
-    launch_owner_d<128>(qbt, grid, p.lds_bytes, s, p, stages);
-  } else {
-    launch_owner_d<64>(qbt, grid, p.lds_bytes, s, p, stages);
-  }
-  return hipGetLastError();
+  const dim3 grid(static_cast<unsigned>(p.n_problems)), block(kOwnThreads);
+  const bool ok = with_step_kernel(head_dim, own_qbt(p.row_chunk), p.rope_pairing != FINCH_ROPE_OFF, [&](auto kern) {
+    hipLaunchKernelGGL(kern, grid, block, p.lds_bytes, s, p, stages);
+  });
+  return ok ? hipGetLastError() : hipErrorInvalidValue;
 }
 
 // The whole loop: n_slots workgroups; step_first is a DEVICE array of n_steps + 1
@@ -432,35 +470,29 @@ hipError_t launch_owner_bf16(int head_dim, const LaunchParams& p, int stages, hi
 hipError_t launch_owner_loop_bf16(int head_dim, const LaunchParams& p, const int* step_first, int n_steps,
                                   int n_slots, hipStream_t s) {
   if (n_slots <= 0 || n_steps <= 0) return hipSuccess;
-  const int qbt = own_qbt(p.row_chunk);
-  if (qbt == 0) return hipErrorInvalidValue;
-  const dim3 grid(static_cast<unsigned>(n_slots));
-  if (head_dim == 128) {
-    launch_owner_loop_d<128>(qbt, grid, p.lds_bytes, s, p, step_first, n_steps);
-  } else {
-    launch_owner_loop_d<64>(qbt, grid, p.lds_bytes, s, p, step_first, n_steps);
-  }
-  return hipGetLastError();
+  const dim3 grid(static_cast<unsigned>(n_slots)), block(kOwnThreads);
+  const bool ok = with_loop_kernel(head_dim, own_qbt(p.row_chunk), p.rope_pairing != FINCH_ROPE_OFF, [&](auto kern) {
+    hipLaunchKernelGGL(kern, grid, block, p.lds_bytes, s, p, step_first, n_steps);
+  });
+  return ok ? hipGetLastError() : hipErrorInvalidValue;
 }
 
 hipError_t set_max_lds_owner(size_t bytes) {
-  const int qbts[4] = {2, 4, 6, 8};
-  for (int i = 0; i < 4; ++i) {
-    hipError_t e = hipFuncSetAttribute(owner_ptr<128>(qbts[i]),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       static_cast<int>(bytes));
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(owner_ptr<64>(qbts[i]), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            static_cast<int>(bytes));
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(owner_loop_ptr<128>(qbts[i]), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            static_cast<int>(bytes));
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(owner_loop_ptr<64>(qbts[i]), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            static_cast<int>(bytes));
-    if (e != hipSuccess) return e;
-  }
-  return hipSuccess;
+  hipError_t err = hipSuccess;
+  const int dims[2] = {128, 64}, qbts[4] = {2, 4, 6, 8};
+  for (int d = 0; d < 2; ++d)
+    for (int q = 0; q < 4; ++q)
+      for (int rot = 0; rot < 2; ++rot) {
+        auto set = [&](auto kern) {
+          const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                   static_cast<int>(bytes));
+          if (e != hipSuccess) err = e;
+        };
+        with_step_kernel(dims[d], qbts[q], rot != 0, set);
+        with_loop_kernel(dims[d], qbts[q], rot != 0, set);
+      }
+  return err;
 }
 
 }  // namespace finch

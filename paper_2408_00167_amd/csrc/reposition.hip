@@ -16,46 +16,15 @@
 #include <cmath>
 
 #include "finch_internal.h"
+#include "reposition_common.h"
 #include "select_common.h"
 
 namespace finch {
 
 namespace {
 
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef rp_u32x4 u32x4;
 constexpr int kRepThreads = 256;
-
-__device__ __forceinline__ float bf16_to_f32(unsigned bits16) { return __uint_as_float(bits16 << 16); }
-__device__ __forceinline__ unsigned f32_to_bf16(float x) {  // round to nearest even; finite inputs
-  const unsigned u = __float_as_uint(x);
-  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
-
-// Element e of a 16-byte piece as float, and back.  E = elements per piece.
-template <int E>
-__device__ __forceinline__ float piece_get(const u32x4& v, int e) {
-  if (E == 4) return __uint_as_float(v[e]);
-  const unsigned w = v[e >> 1];
-  return bf16_to_f32((e & 1) ? (w >> 16) : (w & 0xFFFFu));
-}
-template <int E>
-__device__ __forceinline__ void piece_set(u32x4& v, int e, float x) {
-  if (E == 4) {
-    v[e] = __float_as_uint(x);
-  } else {
-    const unsigned b = f32_to_bf16(x);
-    unsigned w = v[e >> 1];
-    w = (e & 1) ? ((w & 0x0000FFFFu) | (b << 16)) : ((w & 0xFFFF0000u) | b);
-    v[e >> 1] = w;
-  }
-}
-
-// (cos, sin) of shift * theta, theta in radians per position.
-__device__ __forceinline__ void turn(double theta, int shift, float& c, float& s) {
-  const double rev = static_cast<double>(shift) * theta * 0.15915494309189535;  // turns
-  const double frac = rev - rint(rev);                                           // [-0.5, 0.5]
-  sincospif(static_cast<float>(2.0 * frac), &s, &c);
-}
 
 }  // namespace
 
@@ -78,7 +47,6 @@ __global__ __launch_bounds__(kRepThreads) void reposition_rows(LaunchParams prm,
   constexpr int kHalf = SEGS / 2;                      // threads per row
   constexpr int kRowsPerIter = kRepThreads / kHalf;
   constexpr int kIters = kGatherRows / kRowsPerIter;
-  constexpr int D = SEGS * E;
   const int seg = tid % kHalf;
   const int sub = tid / kHalf;
 
@@ -104,16 +72,7 @@ __global__ __launch_bounds__(kRepThreads) void reposition_rows(LaunchParams prm,
 
   // theta of this thread's E channel pairs
   double th[E];
-#pragma unroll
-  for (int e = 0; e < E; ++e) {
-    int u;
-    if (pairing == FINCH_ROPE_INTERLEAVED) {
-      u = e < E / 2 ? (E / 2) * seg + e : (E / 2) * (seg + kHalf) + (e - E / 2);
-    } else {
-      u = E * seg + e;
-    }
-    th[e] = exp2(-2.0 * static_cast<double>(u) / static_cast<double>(D) * log2_base);
-  }
+  pair_thetas<E, kHalf>(pairing, seg, log2_base, th);
 
   const FINCH_GLOBAL u32x4* kc = as_global<u32x4>(pb.k_cache);
   const FINCH_GLOBAL u32x4* kk = as_global<u32x4>(pb.k_chunk);
@@ -141,34 +100,7 @@ __global__ __launch_bounds__(kRepThreads) void reposition_rows(LaunchParams prm,
   for (int it = 0; it < kIters; ++it) {
     const int t = row0 + it * kRowsPerIter + sub;
     if (t < r) {
-      if (pairing != FINCH_ROPE_OFF && shift[it] != 0) {
-        u32x4 a = ka[it], b = kb[it];
-#pragma unroll
-        for (int e = 0; e < E; ++e) {
-          float c, s;
-          turn(th[e], shift[it], c, s);
-          if (pairing == FINCH_ROPE_INTERLEAVED) {
-            // pairs (2e', 2e'+1) inside a piece: the first E/2 in piece a, the rest in b
-            const int e2 = 2 * (e % (E / 2));
-            if (e < E / 2) {
-              const float x = piece_get<E>(a, e2), y = piece_get<E>(a, e2 + 1);
-              piece_set<E>(a, e2, x * c - y * s);
-              piece_set<E>(a, e2 + 1, y * c + x * s);
-            } else {
-              const float x = piece_get<E>(b, e2), y = piece_get<E>(b, e2 + 1);
-              piece_set<E>(b, e2, x * c - y * s);
-              piece_set<E>(b, e2 + 1, y * c + x * s);
-            }
-          } else {
-            // pair (u, u + d/2): element e of piece a with element e of piece b
-            const float x = piece_get<E>(a, e), y = piece_get<E>(b, e);
-            piece_set<E>(a, e, x * c - y * s);
-            piece_set<E>(b, e, y * c + x * s);
-          }
-        }
-        ka[it] = a;
-        kb[it] = b;
-      }
+      if (pairing != FINCH_ROPE_OFF && shift[it] != 0) rotate_pieces<E>(pairing, th, shift[it], ka[it], kb[it]);
       const size_t o = static_cast<size_t>(slot[it]) * SEGS + seg;
       ko[o] = ka[it];
       ko[o + kHalf] = kb[it];

@@ -194,7 +194,7 @@ __global__ __launch_bounds__(kThreads, 4) void colsum_bf16(LaunchParams prm) {
   int b0, b1;
   slice_blocks(N, stream_slices(N, prm.slice_keys), slice, b0, b1);
   const int R = prm.group * pb.n_que;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
   const int t = lane & 31, h = lane >> 5;
   constexpr int kStride = D * 2 + 16;
   char* lds_q = smem;

@@ -60,6 +60,51 @@ def test_step_with_repositioning(dtype, d, group, pairing, order):
     fin.close()
 
 
+@pytest.mark.parametrize("pairing", ["half", "interleaved"])
+@pytest.mark.parametrize("d,group", [(128, 4), (64, 2)])
+def test_one_workgroup_per_problem_repositions_to_ascending_slots(d, group, pairing):
+    say(f"reposition owner d={d} G={group} {pairing}")
+    fin = F.Finch(F.FINCH_BF16, d, group)
+    fin.set_step_path(F.FINCH_PATH_OWNER)
+    fin.set_reposition(PAIRING[pairing], F.FINCH_ORDER_ASCENDING, 10000.0)
+    batch, ts = H.single_step_case(fin, SPECS, torch.bfloat16, d, group, seed=600 + d)
+    fin.step(batch)
+    st = H.validate_single_step(ts, f"owner repos {pairing}", repos=(pairing, "ascending", 10000.0))
+    say(f"  worst rotation error / row max {st['worst_rot']:.2e}")
+    # the per-stage kernels give the same bits
+    fin.set_step_path(F.FINCH_PATH_SEPARATE)
+    b2, t2 = H.single_step_case(fin, SPECS, torch.bfloat16, d, group, seed=600 + d)
+    fin.step(b2)
+    torch.cuda.synchronize()
+    for a, b in zip(ts, t2):
+        assert torch.equal(a["idx"], b["idx"])
+        assert torch.equal(a["k_out"], b["k_out"]) and torch.equal(a["v_out"], b["v_out"])
+    fin.close()
+
+
+def test_whole_loop_with_repositioning_equals_step_by_step():
+    from paper_2408_00167_amd.driver import ChunkLoop
+    w = W.get_workload("C4")
+    fin = F.Finch(F.FINCH_BF16, 128, 4)
+    fin.set_step_path(F.FINCH_PATH_OWNER)
+    fin.set_reposition(F.FINCH_ROPE_HALF, F.FINCH_ORDER_ASCENDING, 500000.0)
+    probs = []
+    for j, n in enumerate([2048, 1300, 1800]):
+        pb = H.make_gpu_problem(w, 0, 0, j, n_cont=n)
+        pb["budget"] = n // 6
+        probs.append(pb)
+    finals = []
+    for per_step in (False, True):
+        loop = ChunkLoop(fin, probs, 512, history=True)
+        loop.run(per_step=per_step)
+        torch.cuda.synchronize()
+        finals.append([tuple(t.clone() for t in loop.final_cache(p)) for p in range(len(probs))] + [loop.idx.clone()])
+    for a, b in zip(finals[0][:-1], finals[1][:-1]):
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    assert torch.equal(finals[0][-1], finals[1][-1])
+    fin.close()
+
+
 def test_shifts_of_hundreds_of_thousands_of_positions():
     """One long chunk: kept keys move up to 3*10^5 positions towards the start, so the
     angle must be reduced before sine and cosine are taken."""
