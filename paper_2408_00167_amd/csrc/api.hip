@@ -531,7 +531,7 @@ finch_status finch_prompt_lse(finch_ctx* ctx, const finch_problem* host_desc,
       return FINCH_ERR_INVALID_ARG;
   }
   if (n == 0) return FINCH_OK;
-  if (static_cast<int64_t>(n) * ((pl.rows_max + 255) / 256) >= (int64_t{1} << 31)) return FINCH_ERR_CAPACITY;
+  if (static_cast<int64_t>(n) * ((pl.rows_max + 63) / 64) >= (int64_t{1} << 31)) return FINCH_ERR_CAPACITY;
   const LaunchParams p = make_params(ctx, dev_desc, n, pl, nullptr);
   hipError_t e;
   {

@@ -5,7 +5,8 @@
 //   lse_extra[i] = log sum_{j <= t} exp(q_i . kq_j / sqrt(d_k))
 // over the prompt's own keys kq, which the scoring kernels add to the row's
 // denominator over the context keys.  The work is tiny (R * n_que / 2 dot
-// products per problem): one thread per row, dot products accumulated in fp64.
+// products per problem): four lanes per row, each with a quarter of the channels,
+// dot products accumulated in fp64.
 #include "finch_internal.h"
 
 namespace finch {
@@ -14,7 +15,7 @@ namespace {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-// Dot product of two rows of D elements stored as 16-byte pieces; E = elements per piece.
+// Dot product of two runs of D elements stored as 16-byte pieces; E = elements per piece.
 template <int D, int E, typename PA, typename PB>
 __device__ __forceinline__ double row_dot(PA a, PB b) {
   double acc[4] = {0.0, 0.0, 0.0, 0.0};  // independent chains; summed in a fixed order
@@ -39,6 +40,8 @@ __device__ __forceinline__ double row_dot(PA a, PB b) {
 
 // lds_rows = prompt keys that fit in the launch's dynamic LDS; problems with at most
 // that many stage them there, longer prompts read them from memory.
+constexpr int kRowsPerGroup = 64;  // rows per workgroup of 256 threads
+
 template <int D, int E>
 __global__ __launch_bounds__(256) void prompt_lse_rows(LaunchParams prm, int blocks_per_problem,
                                                        int lds_rows) {
@@ -47,7 +50,7 @@ __global__ __launch_bounds__(256) void prompt_lse_rows(LaunchParams prm, int blo
   const finch_problem pb = prm.probs[p];
   const int n_que = pb.n_que;
   const int R = prm.group * n_que;
-  const int row0 = (blockIdx.x - p * blocks_per_problem) * 256;
+  const int row0 = (blockIdx.x - p * blocks_per_problem) * kRowsPerGroup;
   if (row0 >= R) return;
   const FINCH_GLOBAL u32x4* kq = as_global<u32x4>(pb.k_que);
   const bool staged = n_que <= lds_rows;
@@ -56,15 +59,19 @@ __global__ __launch_bounds__(256) void prompt_lse_rows(LaunchParams prm, int blo
     for (int i = threadIdx.x; i < n_que * (D / E); i += 256) lkq[i] = kq[i];
     __syncthreads();
   }
-  const int row = row0 + threadIdx.x;
-  if (row >= R) return;
+  // lanes 4i .. 4i+3 share row row0 + i; clamped rows compute and store nothing
+  const int row = min(row0 + (static_cast<int>(threadIdx.x) >> 2), R - 1);
+  const int part = threadIdx.x & 3;
+  constexpr int kPieces = D / E / 4;  // 16-byte pieces per lane
   const int t = row % n_que;
-  const FINCH_GLOBAL u32x4* q = as_global<u32x4>(pb.q) + static_cast<size_t>(row) * (D / E);
+  const FINCH_GLOBAL u32x4* q = as_global<u32x4>(pb.q) + static_cast<size_t>(row) * (D / E) + part * kPieces;
   const double scale = 1.0 / sqrt(static_cast<double>(D));
   double m = -__builtin_inf(), z = 0.0;
   for (int j = 0; j <= t; ++j) {
-    const double dot = staged ? row_dot<D, E>(q, lkq + static_cast<size_t>(j) * (D / E))
-                              : row_dot<D, E>(q, kq + static_cast<size_t>(j) * (D / E));
+    const size_t off = static_cast<size_t>(j) * (D / E) + part * kPieces;
+    double dot = staged ? row_dot<D / 4, E>(q, lkq + off) : row_dot<D / 4, E>(q, kq + off);
+    dot += __shfl_xor(dot, 1);
+    dot += __shfl_xor(dot, 2);
     const double s = dot * scale;
     if (s > m) {
       z = z * exp(m - s) + 1.0;   // exp(-inf) = 0 on the first key
@@ -73,12 +80,13 @@ __global__ __launch_bounds__(256) void prompt_lse_rows(LaunchParams prm, int blo
       z += exp(s - m);
     }
   }
-  as_global_mut<float>(pb.lse_extra)[row] = static_cast<float>(m + log(z));
+  if (part == 0 && row0 + (static_cast<int>(threadIdx.x) >> 2) < R)
+    as_global_mut<float>(pb.lse_extra)[row] = static_cast<float>(m + log(z));
 }
 
 hipError_t launch_prompt_lse(const LaunchParams& p, int head_dim, bool bf16, int rows_max, hipStream_t s) {
   if (p.n_problems == 0 || rows_max <= 0) return hipSuccess;
-  const int bpp = (rows_max + 255) / 256;
+  const int bpp = (rows_max + kRowsPerGroup - 1) / kRowsPerGroup;
   const dim3 grid(static_cast<unsigned>(bpp) * static_cast<unsigned>(p.n_problems)), block(256);
   // prompt keys in LDS: as many as the longest prompt has, up to 48 KB (no opt-in needed)
   const int row_bytes = head_dim * (bf16 ? 2 : 4);
