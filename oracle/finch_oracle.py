@@ -57,6 +57,14 @@ pure-Python triple loop over heads, rows and keys, by a construction in which th
 heads disagree and the layer's choice is known in closed form, by H identical heads
 reproducing the single-head choice, and by closed forms of the schedule.
 
+Conditioning on the chunk's own rows (`key_scores_conditioned`: the paper's
+ablation, rows = chunk tokens with the causal mask, alone or together with the
+prompt rows, and the Method's normalisation read per row).  Pinned by a pure-Python
+loop with the mask written out, by scipy's softmax on the -inf-masked matrix, by
+closed forms (first chunk token, sum of all scores = sum of the row weights), by
+causality (a later key cannot change what earlier rows give) and by the reduction to
+`key_scores` when there are no chunk rows.
+
 Pins: a rotation by zero is the identity bit for bit, rotations add up, pair norms
 are kept, dot products of two rotated vectors depend only on the difference of
 their positions, the closed form (1, 0) -> (cos a, sin a), numpy's complex
@@ -72,7 +80,7 @@ import numpy as np
 
 __all__ = ["widen", "attention_weights", "key_scores", "top_r", "gather_rows",
            "step", "schedule", "compress", "reposition", "rope_frequencies", "rope_rotate",
-           "kept_slots", "compact_repositioned", "prompt_lse", "layer_scores", "step_layer"]
+           "kept_slots", "compact_repositioned", "prompt_lse", "layer_scores", "step_layer", "key_scores_conditioned"]
 
 
 def widen(x: np.ndarray) -> np.ndarray:
@@ -320,3 +328,38 @@ def step_layer(Qs, K_caches, V_caches, K_chunks, V_chunks, r: int, lse_extras=No
     return (per_head, total, idx,
             [gather_rows(idx, K_caches[h], K_chunks[h]) for h in range(H)],
             [gather_rows(idx, V_caches[h], V_chunks[h]) for h in range(H)])
+
+
+def key_scores_conditioned(Q_prompt, Q_doc, K_cache: np.ndarray, K_chunk: np.ndarray, group: int,
+                           lse_extra: Optional[np.ndarray] = None) -> np.ndarray:
+    """Scores when the rows of the attention matrix are not (only) the prompt's (the
+    paper's ablation of the conditioning: self-attention of the document chunk, or
+    of chunk and prompt together, instead of the prompt alone), with the Method's
+    normalisation step.
+
+    The model's input is [cache ; chunk ; prompt].  Q_doc [group * m][d] stacks, head
+    by head, the queries of the m chunk tokens; chunk token i (position c + i) sees
+    the cache and the chunk keys up to itself: c + i + 1 keys.  Q_prompt
+    [group * n_que][d] as in `key_scores` sees all c + m context keys.  Either may be
+    None.  Every row is a softmax over the keys it sees; the normalisation multiplies
+    row i by (keys row i sees) / (m + c) - read per row: it is what offsets the
+    thinner spread of rows that see more keys, and it is 1 for prompt rows - and
+    the score of key j is the sum over the rows that see it.
+    """
+    K = widen(np.concatenate([np.asarray(K_cache), np.asarray(K_chunk)], axis=0))
+    c, m = np.asarray(K_cache).shape[0], np.asarray(K_chunk).shape[0]
+    N = c + m
+    total = np.zeros(N, dtype=np.float64)
+    if Q_prompt is not None:
+        total += key_scores(Q_prompt, K_cache, K_chunk, lse_extra)
+    if Q_doc is not None and m > 0:
+        Qd = widen(Q_doc)
+        assert Qd.shape[0] == group * m
+        S = (Qd @ K.T) / math.sqrt(float(Qd.shape[1]))
+        for row in range(group * m):
+            i = row % m
+            vis = c + i + 1
+            s = S[row, :vis]
+            e = np.exp(s - s.max())
+            total[:vis] += (e / e.sum()) * (vis / float(N))
+    return total

@@ -566,4 +566,73 @@ def pin_constant_budget_schedule(O):
     assert O.schedule(131072, 4096, 1408)[-1] == 1408 and O.schedule(131072, 4096, 1408)[0] == 44
 
 
+def pin_conditioned_on_document_rows(O):
+    from scipy.special import softmax
+    rng = np.random.default_rng(61)
+    d, G, nq, c, m = 8, 2, 3, 4, 6
+    N = c + m
+    Qp = rng.standard_normal((G * nq, d)).astype(np.float32)
+    Qd = rng.standard_normal((G * m, d)).astype(np.float32)
+    Kc = rng.standard_normal((c, d)).astype(np.float32)
+    Kk = rng.standard_normal((m, d)).astype(np.float32)
+    K = np.concatenate([Kc, Kk]).astype(np.float64)
+    # scipy on the explicitly masked matrix, rows weighted by (visible keys) / N
+    S = Qd.astype(np.float64) @ K.T / math.sqrt(d)
+    vis = np.array([c + (row % m) + 1 for row in range(G * m)])
+    for row in range(G * m):
+        S[row, vis[row]:] = -np.inf
+    A = softmax(S, axis=1) * (vis / N)[:, None]
+    want_doc = A.sum(axis=0)
+    got_doc = O.key_scores_conditioned(None, Qd, Kc, Kk, G)
+    assert np.abs(got_doc - want_doc).max() < 1e-13
+    # pure-Python loops
+    brute = [0.0] * N
+    for row in range(G * m):
+        i = row % m
+        q = list(map(float, Qd[row]))
+        logits = [sum(a * b for a, b in zip(q, map(float, K[j]))) / math.sqrt(d) for j in range(c + i + 1)]
+        mx = max(logits)
+        e = [math.exp(x - mx) for x in logits]
+        z = sum(e)
+        for j in range(c + i + 1):
+            brute[j] += e[j] / z * (c + i + 1) / N
+    assert max(abs(a - b) for a, b in zip(got_doc, brute)) < 1e-12
+    # both row sets: the sum of the two; prompt rows carry weight 1
+    both = O.key_scores_conditioned(Qp, Qd, Kc, Kk, G)
+    assert np.abs(both - (want_doc + O.key_scores(Qp, Kc, Kk))).max() < 1e-13
+    assert np.abs(O.key_scores_conditioned(Qp, None, Kc, Kk, G) - O.key_scores(Qp, Kc, Kk)).max() < 1e-15
+    # all scores add up to the sum of the row weights
+    assert abs(got_doc.sum() - (vis / N).sum()) < 1e-12
+    # no cache: the same by hand over the chunk alone
+    first = O.key_scores_conditioned(None, Qd, Kc[:0], Kk, G)
+    only_first_rows = np.zeros(m)
+    S0 = Qd.astype(np.float64) @ Kk.astype(np.float64).T / math.sqrt(d)
+    for row in range(G * m):
+        i = row % m
+        s = S0[row, :i + 1]
+        e = np.exp(s - s.max())
+        only_first_rows[:i + 1] += e / e.sum() * (i + 1) / m
+    assert np.abs(first - only_first_rows).max() < 1e-13
+    # closed form: a chunk of one token sees only itself and gives its key weight 1
+    one = O.key_scores_conditioned(None, Qd[:1], Kc[:0], Kk[:1], 1)
+    assert abs(one[0] - 1.0) < 1e-15
+    # causality: changing the LAST chunk key changes nothing that earlier chunk rows give:
+    # with only the first m-1 tokens' rows, the result is the same for either last key
+    Kk2 = Kk.copy()
+    Kk2[-1] += 3.0
+    rows_but_last = np.array([r for r in range(G * m) if r % m != m - 1])
+    def partial(Kx):
+        Kall = np.concatenate([Kc, Kx]).astype(np.float64)
+        out = np.zeros(N)
+        Sx = Qd.astype(np.float64) @ Kall.T / math.sqrt(d)
+        for row in rows_but_last:
+            v = c + (row % m) + 1
+            e = np.exp(Sx[row, :v] - Sx[row, :v].max())
+            out[:v] += e / e.sum() * v / N
+        return out
+    last_rows_a = O.key_scores_conditioned(None, Qd, Kc, Kk, G) - partial(Kk)
+    assert np.abs(partial(Kk) - partial(Kk2)).max() < 1e-15
+    assert np.abs(last_rows_a).max() > 1e-3 and (last_rows_a >= -1e-15).all()
+
+
 ALL_PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_") and callable(v)]

@@ -14,6 +14,11 @@ SRC = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
                    "oracle", "finch_oracle.py")
 
 MUTATIONS = {
+    "doc_rows_not_causal": ("            vis = c + i + 1\n", "            vis = N\n"),
+    "doc_rows_exclude_self": ("            vis = c + i + 1\n", "            vis = c + i\n"),
+    "doc_rows_token_major": ("            i = row % m\n            vis", "            i = row // group\n            vis"),
+    "doc_rows_not_normalised": ("total[:vis] += (e / e.sum()) * (vis / float(N))", "total[:vis] += (e / e.sum())"),
+    "doc_rows_normalised_inversely": ("total[:vis] += (e / e.sum()) * (vis / float(N))", "total[:vis] += (e / e.sum()) * (float(N) / vis)"),
     "layer_keeps_first_head_only": ("for s in per_head:\n        total = total + np.asarray(s, dtype=np.float64)",
                                     "for s in per_head[:1]:\n        total = total + np.asarray(s, dtype=np.float64)"),
     "layer_mean_of_maxima": ("    idx = top_r(total, r)\n    return (per_head", "    idx = top_r(per_head[0], r)\n    return (per_head"),
