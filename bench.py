@@ -100,6 +100,9 @@ def main() -> int:
                     help="L > 1: one selection per run of L problems (the KV heads of a layer)")
     ap.add_argument("--constant-budget", action="store_true",
                     help="keep the whole budget k from the first step on")
+    ap.add_argument("--doc-rows", action="store_true",
+                    help="scoring also takes the rows of each chunk's own tokens (causal mask); "
+                         "about G*m more rows per problem, so use few --steps")
     ap.add_argument("--exact-denominator", action="store_true",
                     help="softmax denominators include the prompt's own keys (random ones here)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -144,6 +147,8 @@ def main() -> int:
         p = W.make_problem(w, b, l, g, device=dev)
         probs.append(dict(Q=p["Q"], K=p["K"], V=p["V"], n_que=w.requests[b].n_que,
                           budget=w.requests[b].budget))
+        if args.doc_rows:
+            probs[-1]["Q_doc"] = torch.randn(w.group, w.chunk, w.head_dim, device=dev).to(p["K"].dtype)
         if args.exact_denominator:
             probs[-1]["K_que"] = torch.randn(w.requests[b].n_que, w.head_dim, device=dev).to(p["K"].dtype)
     loop = ChunkLoop(fin, probs, w.chunk, history=False, want_scores=False,
@@ -224,7 +229,8 @@ def main() -> int:
                    "head_dim": w.head_dim, "group": w.group,
                    "path": args.path, "calls": "finch_step per chunk" if args.per_step else "finch_loop",
                    "reposition": args.reposition, "order": args.order,
-                   "exact_denominator": args.exact_denominator, "layer_group": args.layer_group,
+                   "exact_denominator": args.exact_denominator, "doc_rows": args.doc_rows,
+                   "layer_group": args.layer_group,
                    "constant_budget": args.constant_budget,
                    "prompt_rows": [w.rows(r) for r in w.requests][:4],
                    "budget": [r.budget for r in w.requests][:4], "keys_scored": keys},

@@ -71,6 +71,9 @@ typedef struct {
   float* lse_extra;    /* [G*n_que] natural-log log-sum-exp, per prompt row, of logits
                           over keys that are not candidates; NULL = none.  Written by
                           finch_prompt_lse, read by the scoring of every other call   */
+  const void* q_doc;   /* [G*m][d] queries of the chunk's own tokens, head 0's m rows,
+                          head 1's, ...; NULL = rows from the prompt only (see
+                          "Conditioning on the chunk's own rows" below)               */
 } finch_problem;
 
 /* Row bases (q, k_*, v_*, *_out) must be 16-byte aligned, scores and idx 4-byte. */
@@ -103,6 +106,20 @@ finch_status finch_score(finch_ctx* ctx, const finch_problem* host_desc,
  * and n_que and writes desc.lse_extra (all three required); no workspace. */
 finch_status finch_prompt_lse(finch_ctx* ctx, const finch_problem* host_desc,
                               const finch_problem* dev_desc, int32_t n_problems, void* stream);
+
+/* Conditioning on the chunk's own rows (the paper's ablation of the conditioning:
+ * self-attention of the document chunk, alone or together with the prompt, in
+ * place of the prompt-guided sub-matrix, with the Method's normalisation step).
+ * With desc.q_doc the scoring of finch_score, finch_step and finch_loop adds, for
+ * every head g and chunk token i, the row q_doc[g*m + i]: it sees the cache and the
+ * chunk keys up to itself (the c + i + 1 first candidates; the model's input is
+ * [cache ; chunk ; prompt] under the causal mask), its weights are a softmax over
+ * those, and the normalisation step multiplies them by (c + i + 1) / (c + m) - read
+ * per row: the factor offsets the thinner spread of rows that see more keys and is
+ * 1 for prompt rows.  scores[j] is the sum over all rows that see key j.  desc.q
+ * may then be NULL (document rows only; n_que is ignored).  bf16 only, and always
+ * through the one-workgroup-per-problem kernels whatever the batch size; the work
+ * grows from G*n_que to G*(n_que + m) rows per problem. */
 
 /* Selection (Method: t = top-r(A_agg, r)): reads desc.scores (any finite fp32),
  * writes the indices of the min(r, c+m) largest into desc.idx in ascending order;

@@ -67,7 +67,8 @@ class finch_problem(ctypes.Structure):
                 ("k_out", ctypes.c_void_p), ("v_out", ctypes.c_void_p),
                 ("scores", ctypes.c_void_p), ("idx", ctypes.c_void_p),
                 ("n_que", ctypes.c_int32), ("c", ctypes.c_int32), ("m", ctypes.c_int32),
-                ("r", ctypes.c_int32), ("k_que", ctypes.c_void_p), ("lse_extra", ctypes.c_void_p)]
+                ("r", ctypes.c_int32), ("k_que", ctypes.c_void_p), ("lse_extra", ctypes.c_void_p),
+                ("q_doc", ctypes.c_void_p)]
 
 
 _lib = None
@@ -249,7 +250,7 @@ class Batch:
     """A descriptor array on the host and its copy on the device.
 
     `problems` is a sequence of dicts with tensors q, k_cache, v_cache, k_chunk,
-    v_chunk, k_out, v_out, scores, idx, and optionally k_que, lse_extra (any may be
+    v_chunk, k_out, v_out, scores, idx, and optionally k_que, lse_extra, q_doc (any may be
     None where the C ABI allows NULL) and ints n_que, c, m, r.  The tensors are only read for their device
     pointers; the caller keeps them alive.
     """
@@ -262,7 +263,7 @@ class Batch:
         for i, pb in enumerate(problems):
             d = self.host[i]
             for name in ("q", "k_cache", "v_cache", "k_chunk", "v_chunk", "k_out", "v_out",
-                         "scores", "idx", "k_que", "lse_extra"):
+                         "scores", "idx", "k_que", "lse_extra", "q_doc"):
                 setattr(d, name, _ptr(pb.get(name)))
             d.n_que, d.c, d.m, d.r = int(pb["n_que"]), int(pb["c"]), int(pb["m"]), int(pb["r"])
         raw = bytes(self.host)[: n * ctypes.sizeof(finch_problem)]

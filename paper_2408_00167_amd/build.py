@@ -13,12 +13,11 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 LIB_PATH = os.path.join(PKG_DIR, "libfinch.so")
 
-SOURCES = ["api.hip", "score_bf16.hip", "owner_bf16.hip", "score_f32.hip", "select.hip", "reposition.hip", "prompt_lse.hip",
+SOURCES = ["api.hip", "score_bf16.hip", "owner_bf16.hip", "owner_doc_bf16.hip", "score_f32.hip", "select.hip", "reposition.hip", "prompt_lse.hip",
            "gather.hip"]
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-    "-fgpu-rdc" if False else "-fno-gpu-rdc",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     # packed fp32 instructions are kept out of generated code on this target
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
@@ -32,18 +31,39 @@ def hipcc_path() -> str:
     return "hipcc"
 
 
-def build_library(verbose: bool = True, extra_flags=()) -> str:
-    cmd = [hipcc_path(), *HIPCC_FLAGS, *extra_flags, "-I", INCLUDE, "-I", CSRC,
-           *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB_PATH]
-    if verbose:
-        print(" ".join(cmd), flush=True)
+def _run(cmd, verbose: bool) -> None:
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(ln for ln in proc.stdout.splitlines()
                     if "is not a recognized feature for this target" not in ln)
     if verbose and out.strip():
         print(out, flush=True)
     if proc.returncode != 0:
-        raise RuntimeError(f"hipcc failed ({proc.returncode}):\n{out}")
+        raise RuntimeError(f"hipcc failed ({proc.returncode}): {' '.join(cmd)}\n{out}")
+
+
+def build_library(verbose: bool = True, extra_flags=(), jobs: int = 0) -> str:
+    """Compiles every source to an object (in parallel), then links libfinch.so."""
+    from concurrent.futures import ThreadPoolExecutor
+    obj_dir = os.path.join(PKG_DIR, "_build")
+    os.makedirs(obj_dir, exist_ok=True)
+    hipcc = hipcc_path()
+    jobs = jobs or min(len(SOURCES), max(1, (os.cpu_count() or 2) - 1), 8)
+    objs = [os.path.join(obj_dir, s.replace(".hip", ".o")) for s in SOURCES]
+
+    def compile_one(pair):
+        src, obj = pair
+        cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-I", INCLUDE, "-I", CSRC, "-c",
+               os.path.join(CSRC, src), "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        _run(cmd, verbose)
+
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        list(pool.map(compile_one, zip(SOURCES, objs)))
+    link = [hipcc, "--offload-arch=gfx950", "-fno-gpu-rdc", "-shared", "-fPIC", *objs, "-o", LIB_PATH]
+    if verbose:
+        print(" ".join(link), flush=True)
+    _run(link, verbose)
     return LIB_PATH
 
 

@@ -42,6 +42,7 @@ struct Plan {
   int32_t n_max = 0, rows_max = 0, rpad_max = 0, r_max = 0, tiles_max = 0, row_chunk = 32;
   int32_t score_stride = 0;
   bool own_ok = false;    // the batch can run with one workgroup per problem
+  bool has_doc = false;   // some problem takes rows from the chunk's own tokens (q_doc)
   int32_t own_row_chunk = 32;
   size_t own_lds = 0;
   size_t lds_bytes = 0;
@@ -77,10 +78,19 @@ finch_status make_plan(const finch_ctx* ctx, const finch_problem* hd, int32_t n_
   int64_t n_max = 0, rows_max = 0, r_max = 0;
   for (int32_t i = 0; i < n; ++i) {
     const finch_problem& pb = hd[i];
-    if (pb.n_que < 1 || pb.c < 0 || pb.m < 0 || pb.r < 0) return FINCH_ERR_INVALID_ARG;
+    // prompt rows are optional when the chunk's own rows are given
+    const bool prompt_rows = pb.q != nullptr || pb.q_doc == nullptr;
+    if ((prompt_rows && pb.n_que < 1) || pb.n_que < 0 || pb.c < 0 || pb.m < 0 || pb.r < 0)
+      return FINCH_ERR_INVALID_ARG;
     const int64_t N = static_cast<int64_t>(pb.c) + pb.m;
-    const int64_t R = static_cast<int64_t>(G) * pb.n_que;
+    int64_t R = prompt_rows ? static_cast<int64_t>(G) * pb.n_que : 0;
     if (N > (1 << 24) || R > (1 << 20)) return FINCH_ERR_CAPACITY;
+    if (pb.q_doc) {
+      // staged a chunk of at most kOwnerMaxRowChunk rows at a time
+      pl.has_doc = true;
+      const int64_t dr = pb.m < finch::kOwnerMaxRowChunk ? pb.m : finch::kOwnerMaxRowChunk;
+      if (dr > R) R = dr;
+    }
     if (N > n_max) n_max = N;
     if (R > rows_max) rows_max = R;
     const int64_t rr = pb.r < N ? pb.r : N;
@@ -136,7 +146,9 @@ finch_status validate(const finch_ctx* ctx, const finch_problem* hd, int32_t n, 
     const int64_t rr = pb.r < N ? pb.r : N;
     if (need & kNeedQK) {
       if (N > 0) {
-        if (!pb.q || !aligned(pb.q, 16)) return FINCH_ERR_INVALID_ARG;
+        if (!pb.q && !pb.q_doc) return FINCH_ERR_INVALID_ARG;
+        if (pb.q && !aligned(pb.q, 16)) return FINCH_ERR_INVALID_ARG;
+        if (pb.q_doc && !aligned(pb.q_doc, 16)) return FINCH_ERR_INVALID_ARG;
         if (pb.c > 0 && (!pb.k_cache || !aligned(pb.k_cache, 16))) return FINCH_ERR_INVALID_ARG;
         if (pb.m > 0 && (!pb.k_chunk || !aligned(pb.k_chunk, 16))) return FINCH_ERR_INVALID_ARG;
       }
@@ -249,6 +261,7 @@ bool owner_wanted(const finch_ctx* ctx, const Plan& pl, int32_t n) {
   if (!pl.own_ok || n <= 0 || ctx->repos.order != FINCH_ORDER_ASCENDING || ctx->layer_group > 1)
     return false;
   if (ctx->step_path == FINCH_PATH_OWNER) return true;
+  if (pl.has_doc) return ctx->step_path == FINCH_PATH_AUTO;  // the only kernels with those rows
   if (ctx->step_path != FINCH_PATH_AUTO) return false;
   const int64_t cu = ctx->n_cu > 0 ? ctx->n_cu : 256;
   const int64_t rounds = (n + cu - 1) / cu;
@@ -261,7 +274,8 @@ finch_status run_owner(finch_ctx* ctx, LaunchParams p, const Plan& pl, int stage
   hipError_t e;
   {
     ProfScope ps(ctx, FINCH_KERNEL_OWNER, s);
-    e = finch::launch_owner_bf16(ctx->cfg.head_dim, p, stages, s);
+    e = pl.has_doc ? finch::launch_owner_doc_bf16(ctx->cfg.head_dim, p, stages, s)
+                   : finch::launch_owner_bf16(ctx->cfg.head_dim, p, stages, s);
   }
   return e == hipSuccess ? FINCH_OK : hip_fail(ctx, e);
 }
@@ -272,7 +286,7 @@ finch_status run_score(finch_ctx* ctx, const LaunchParams& p, const Plan& pl, hi
   const int d = ctx->cfg.head_dim;
   const bool bf16 = ctx->cfg.dtype == FINCH_BF16;
   if (owner_wanted(ctx, pl, p.n_problems)) return run_owner(ctx, p, pl, /*stages=*/0, s);
-  if (ctx->step_path == FINCH_PATH_OWNER) return FINCH_ERR_UNSUPPORTED;
+  if (ctx->step_path == FINCH_PATH_OWNER || pl.has_doc) return FINCH_ERR_UNSUPPORTED;
   {
     ProfScope ps(ctx, FINCH_KERNEL_ROWSTATS, s);
     e = bf16 ? finch::launch_rowstats_bf16(d, p, pl.lds_bytes, s)
@@ -395,6 +409,7 @@ finch_status finch_create(const finch_config* cfg, finch_ctx** out) {
                                  : finch::set_max_lds_f32(ctx->max_lds);
   }
   if (e == hipSuccess && cfg->dtype == FINCH_BF16) e = finch::set_max_lds_owner(ctx->max_lds);
+  if (e == hipSuccess && cfg->dtype == FINCH_BF16) e = finch::set_max_lds_owner_doc(ctx->max_lds);
   // the re-positioning kernel also has a little static LDS
   if (e == hipSuccess) e = finch::set_max_lds_reposition(ctx->max_lds - 1024);
   if (e != hipSuccess) {
@@ -586,7 +601,7 @@ finch_status finch_step(finch_ctx* ctx, const finch_problem* host_desc,
   const LaunchParams p = make_params(ctx, dev_desc, n, pl, ws);
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (pl.tiles_max > 0 && owner_wanted(ctx, pl, n)) return run_owner(ctx, p, pl, /*stages=*/1, s);
-  if (ctx->step_path == FINCH_PATH_OWNER && pl.tiles_max > 0) return FINCH_ERR_UNSUPPORTED;
+  if ((ctx->step_path == FINCH_PATH_OWNER || pl.has_doc) && pl.tiles_max > 0) return FINCH_ERR_UNSUPPORTED;
   if ((st = run_score(ctx, p, pl, s)) != FINCH_OK) return st;
   if (pl.r_max == 0) return FINCH_OK;
   if ((st = run_select(ctx, p, pl, ws, s)) != FINCH_OK) return st;
@@ -628,11 +643,13 @@ finch_status finch_loop(finch_ctx* ctx, const finch_problem* host_desc, const fi
     hipError_t e;
     {
       ProfScope ps(ctx, FINCH_KERNEL_OWNER, s);
-      e = finch::launch_owner_loop_bf16(ctx->cfg.head_dim, p, dev_step_first, n_steps, n_slots, s);
+      e = pl.has_doc
+              ? finch::launch_owner_loop_doc_bf16(ctx->cfg.head_dim, p, dev_step_first, n_steps, n_slots, s)
+              : finch::launch_owner_loop_bf16(ctx->cfg.head_dim, p, dev_step_first, n_steps, n_slots, s);
     }
     return e == hipSuccess ? FINCH_OK : hip_fail(ctx, e);
   }
-  if (ctx->step_path == FINCH_PATH_OWNER) return FINCH_ERR_UNSUPPORTED;
+  if (ctx->step_path == FINCH_PATH_OWNER || pl.has_doc) return FINCH_ERR_UNSUPPORTED;
   // one finch_step per step; a step's plan never needs more workspace than the loop's
   for (int32_t i = 0; i < n_steps; ++i) {
     const int32_t f = host_step_first[i], cnt = host_step_first[i + 1] - f;

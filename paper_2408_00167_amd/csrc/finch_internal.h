@@ -72,6 +72,11 @@ hipError_t launch_owner_bf16(int head_dim, const LaunchParams& p, int stages, hi
 hipError_t launch_owner_loop_bf16(int head_dim, const LaunchParams& p, const int* step_first,
                                   int n_steps, int n_slots, hipStream_t s);
 hipError_t set_max_lds_owner(size_t bytes);
+// the same with rows of the chunk's own tokens (desc.q_doc)
+hipError_t launch_owner_doc_bf16(int head_dim, const LaunchParams& p, int stages, hipStream_t s);
+hipError_t launch_owner_loop_doc_bf16(int head_dim, const LaunchParams& p, const int* step_first,
+                                      int n_steps, int n_slots, hipStream_t s);
+hipError_t set_max_lds_owner_doc(size_t bytes);
 // Raise the dynamic-LDS limit of the scoring kernels of one dtype to `bytes`.
 hipError_t set_max_lds_bf16(size_t bytes);
 hipError_t set_max_lds_f32(size_t bytes);

@@ -1,0 +1,543 @@
+// One workgroup per problem for a whole prefill step, bf16 Q/K/V on gfx950: scoring
+// pass 1, the merge of the row statistics, scoring pass 2, top-r and compaction
+// (Method: attention of the prompt rows over cache + chunk keys, sum over heads and
+// prompt rows, t = top-r(A_agg, r), Managing the Cache) run back to back inside the
+// workgroup that owns the problem.
+//
+// Nothing is exchanged between workgroups, so there are no kernel boundaries, no
+// atomics on device memory and no waits: the row statistics are merged in LDS, the
+// scores a workgroup wrote are read back by itself (top-r), and so are the indices
+// (compaction).  The keys are read a second time right after the first pass, while
+// the memory-side cache still holds most of them.  Workgroups are 8 waves (two per
+// SIMD, up to 256 registers each), one per CU; the batch should have about as many problems as the chip has CUs (or a
+// multiple), which the host checks before it picks this path.
+//
+// The arithmetic (and therefore every output bit of scores given the same block
+// assignment rules) follows the two-pass kernels: MFMA 32x32x16 bf16 with one
+// prompt row per lane, log2-domain softmax, pass 1 with a fixed assignment of key
+// blocks to waves, pass 2 with key blocks handed out by an LDS counter.
+//
+// Templates of the one-workgroup-per-problem kernels; instantiated by
+// owner_bf16.hip (prompt rows only) and owner_doc_bf16.hip (rows of the chunk's own
+// tokens as well).
+#pragma once
+
+#include "reposition_common.h"
+#include "score_common.h"
+#include "select_common.h"
+
+namespace finch {
+
+namespace {
+
+constexpr int kOwnThreads = 512;
+constexpr int kOwnWaves = kOwnThreads / 64;
+
+__device__ __forceinline__ int own_next_block(int* counter, int lane) {
+  int v = 0;
+  if (lane == 0) v = atomicAdd(counter, 1);
+  return __builtin_amdgcn_readfirstlane(v);
+}
+
+// Copy rows idx[0..r) of [cache ; chunk] of K and V into k_out / v_out.  `lidx`
+// (LDS) or `gidx` (memory, written by this workgroup) holds the indices; with
+// `identity` row t is simply candidate t.
+template <int SEGS>
+__device__ __forceinline__ void own_gather(const finch_problem& pb, int N, int r, const int* lidx,
+                                           const FINCH_GLOBAL int* gidx, bool identity, int tid) {
+  const FINCH_GLOBAL u32x4* kc = as_global<u32x4>(pb.k_cache);
+  const FINCH_GLOBAL u32x4* kk = as_global<u32x4>(pb.k_chunk);
+  const FINCH_GLOBAL u32x4* vc = as_global<u32x4>(pb.v_cache);
+  const FINCH_GLOBAL u32x4* vk = as_global<u32x4>(pb.v_chunk);
+  FINCH_GLOBAL u32x4* ko = as_global_mut<u32x4>(pb.k_out);
+  FINCH_GLOBAL u32x4* vo = as_global_mut<u32x4>(pb.v_out);
+  constexpr int kRowsPerIter = kOwnThreads / SEGS;
+  constexpr int kUnroll = 8;
+  const int seg = tid % SEGS, sub = tid / SEGS;
+  for (int row0 = 0; row0 < r; row0 += kRowsPerIter * kUnroll) {
+    u32x4 kv[kUnroll], vv[kUnroll];
+#pragma unroll
+    for (int it = 0; it < kUnroll; ++it) {
+      const int t = min(row0 + it * kRowsPerIter + sub, r - 1);
+      int j = identity ? t : (lidx ? lidx[t] : gidx[t]);
+      j = min(max(j, 0), N - 1);
+      const bool cached = j < pb.c;
+      const size_t off = static_cast<size_t>(cached ? j : j - pb.c) * SEGS + seg;
+      kv[it] = (cached ? kc : kk)[off];
+      vv[it] = (cached ? vc : vk)[off];
+    }
+#pragma unroll
+    for (int it = 0; it < kUnroll; ++it) {
+      const int t = row0 + it * kRowsPerIter + sub;
+      if (t < r) {
+        ko[static_cast<size_t>(t) * SEGS + seg] = kv[it];
+        vo[static_cast<size_t>(t) * SEGS + seg] = vv[it];
+      }
+    }
+  }
+}
+
+// The same with the kept keys re-positioned to their (ascending) slots: row t is
+// turned by t - idx[t] positions while it is copied.  A thread owns two pieces of
+// a row, d/2 channels apart, i.e. both partners of its channel pairs.
+template <int SEGS>
+__device__ __forceinline__ void own_gather_rot(const finch_problem& pb, int N, int r, const int* lidx,
+                                               const FINCH_GLOBAL int* gidx, bool identity, int pairing,
+                                               double log2_base, int tid) {
+  constexpr int kHalf = SEGS / 2, E = 8;
+  const FINCH_GLOBAL u32x4* kc = as_global<u32x4>(pb.k_cache);
+  const FINCH_GLOBAL u32x4* kk = as_global<u32x4>(pb.k_chunk);
+  const FINCH_GLOBAL u32x4* vc = as_global<u32x4>(pb.v_cache);
+  const FINCH_GLOBAL u32x4* vk = as_global<u32x4>(pb.v_chunk);
+  FINCH_GLOBAL u32x4* ko = as_global_mut<u32x4>(pb.k_out);
+  FINCH_GLOBAL u32x4* vo = as_global_mut<u32x4>(pb.v_out);
+  constexpr int kRowsPerIter = kOwnThreads / kHalf;
+  constexpr int kUnroll = 4;
+  const int seg = tid % kHalf, sub = tid / kHalf;
+  double th[E];
+  pair_thetas<E, kHalf>(pairing, seg, log2_base, th);
+  for (int row0 = 0; row0 < r; row0 += kRowsPerIter * kUnroll) {
+    u32x4 ka[kUnroll], kb[kUnroll], va[kUnroll], vb[kUnroll];
+    int shift[kUnroll];
+#pragma unroll
+    for (int it = 0; it < kUnroll; ++it) {
+      const int t = min(row0 + it * kRowsPerIter + sub, r - 1);
+      int j = identity ? t : (lidx ? lidx[t] : gidx[t]);
+      j = min(max(j, 0), N - 1);
+      shift[it] = t - j;
+      const bool cached = j < pb.c;
+      const size_t off = static_cast<size_t>(cached ? j : j - pb.c) * SEGS + seg;
+      ka[it] = (cached ? kc : kk)[off];
+      kb[it] = (cached ? kc : kk)[off + kHalf];
+      va[it] = (cached ? vc : vk)[off];
+      vb[it] = (cached ? vc : vk)[off + kHalf];
+    }
+#pragma unroll
+    for (int it = 0; it < kUnroll; ++it) {
+      const int t = row0 + it * kRowsPerIter + sub;
+      if (t < r) {
+        if (shift[it] != 0) rotate_pieces<E>(pairing, th, shift[it], ka[it], kb[it]);
+        const size_t o = static_cast<size_t>(t) * SEGS + seg;
+        ko[o] = ka[it];
+        ko[o + kHalf] = kb[it];
+        vo[o] = va[it];
+        vo[o + kHalf] = vb[it];
+      }
+    }
+  }
+}
+
+}  // namespace
+
+// One step of one problem by the whole workgroup.  QBT = row blocks (of 32 prompt
+// rows) per pass over the keys the code is compiled for; prm.row_chunk <= 32 * QBT.
+// stages: 0 = scores only, 1 = scores, top-r and compaction.  `staged_q` names the
+// prompt block whose rows are in LDS from the previous step of the same launch (or
+// nullptr); inputs do not change during a launch, so the same pointer and row
+// count mean the same rows and the copy is skipped.  Ends with every thread past
+// its last access to LDS only after the next barrier: callers that go on to
+// another step must put a barrier in between.
+template <int D, int QBT, bool ROT, bool DOC>
+__device__ __forceinline__ void own_step_body(const LaunchParams& prm, const finch_problem& pb, int slot,
+                                              int stages, char* smem, const void*& staged_q,
+                                              int& staged_rows) {
+  const int N = pb.c + pb.m;
+  if (N == 0) return;
+  const int Rp = (DOC && !pb.q) ? 0 : prm.group * pb.n_que;  // prompt rows
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int t = lane & 31, h = lane >> 5;
+  constexpr int kStride = D * 2 + 16;
+  const int RC = prm.row_chunk;
+  char* lds_q = smem;
+  float2* wstats = reinterpret_cast<float2*>(smem + RC * kStride);                 // [waves][RC]
+  float* lds_lse = reinterpret_cast<float*>(smem + RC * (kStride + kOwnWaves * 8));  // [RC]
+  int* sh_next = reinterpret_cast<int*>(smem + RC * (kStride + kOwnWaves * 8 + 4));
+  const KeySource ks = {static_cast<const char*>(pb.k_cache), static_cast<const char*>(pb.k_chunk), pb.c};
+  const int nb = (N + 31) >> 5;
+  const float sc = prm.scale_log2;
+  float* gscores = pb.scores ? pb.scores : prm.ws_scores + static_cast<size_t>(slot) * prm.score_stride;
+  FINCH_GLOBAL float* dst = as_global_mut<float>(gscores);
+
+  // Row chunks: the prompt rows first (they see every key, so they initialise all
+  // scores), then, in DOC kernels, the rows of the chunk's own tokens, head by head
+  // and from the last tokens to the first (the last ones see every key as well).
+  const int n_pchunks = (Rp + RC - 1) / RC;
+  const int dper = (DOC && pb.q_doc && pb.m > 0) ? (pb.m + RC - 1) / RC : 0;
+  const int n_chunks = n_pchunks + prm.group * dper;
+  for (int ch = 0; ch < n_chunks; ++ch) {
+    // rows [row0, row0 + rows) of `qsrc` (R rows in all); row i of the chunk sees the
+    // keys below lim0 + lim_step * i
+    const void* qsrc = pb.q;
+    int R = Rp, row0 = ch * RC, lim0 = N, lim_step = 0;
+    if (DOC && ch >= n_pchunks) {
+      const int dc = ch - n_pchunks;
+      const int g = dc / dper;
+      row0 = (dper - 1 - (dc - g * dper)) * RC;
+      qsrc = static_cast<const char*>(pb.q_doc) + static_cast<size_t>(g) * pb.m * (D * 2);
+      R = pb.m;
+      lim0 = pb.c + row0 + 1;
+      lim_step = 1;
+    }
+    const int rows = min(RC, round_up32(R - row0));
+    const int QB = rows >> 5;
+    const bool first_chunk = ch == 0;
+    // key blocks any row of the chunk sees
+    const int nbc = DOC ? (min(N, lim0 + lim_step * (min(row0 + rows, R) - 1 - row0)) + 31) >> 5 : nb;
+    // smallest and largest limit of row block q, and this lane's own in it
+    auto lim_lo = [&](int q) { return lim0 + lim_step * (q * 32); };
+    auto lim_hi = [&](int q) { return lim0 + lim_step * (q * 32 + 31); };
+    auto lim_mine = [&](int q) { return min(N, lim0 + lim_step * (q * 32 + t)); };
+    bf16x8 ka[D / 16], kb[D / 16];
+    int b = wave;
+    if (b < nbc) load_k_block<D>(ks, N, b << 5, lane, ka);  // requested before Q is staged
+    if (!(R <= RC && staged_q == qsrc && staged_rows == R)) {
+      stage_q<D, kOwnThreads>(qsrc, R, row0, rows, lds_q, tid);
+      __syncthreads();
+    }
+    staged_q = nullptr;
+
+    // ---- pass 1: running (reference, sum exp2) per prompt row, fixed block assignment
+    {
+      float m_run[QBT], z_run[QBT];
+#pragma unroll
+      for (int q = 0; q < QBT; ++q) {
+        m_run[q] = -kInf;
+        z_run[q] = 0.f;
+      }
+      // The reference of a row only has to keep exp2 in range: it is taken from the
+      // wave's first key block and moved (sum rescaled) only when a block's sum shows
+      // that its logits lie far above it.
+      // (bit q: row block q has been through at least one visible key block)
+      unsigned seeded = 0;
+      // statistics of one 32 x 32 logit block
+      auto tile_stats = [&](f32x16 a, int q, int kbase) {
+        if (kbase + 32 > (DOC ? min(N, lim_lo(q)) : N)) {  // keys this row does not see, or past the end
+          const int lim = DOC ? lim_mine(q) : N;
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            if (kbase + acc_key(v, h) >= lim) a[v] = -kInf;
+        }
+        float z = 0.f;
+        const bool was_seeded = (seeded >> q) & 1u;
+        bool move = !was_seeded;
+        if (was_seeded) {
+          const float mu = (m_run[q] == -kInf) ? 0.f : m_run[q];
+#pragma unroll
+          for (int v = 0; v < 16; ++v) z += fast_exp2(__builtin_fmaf(a[v], sc, -mu));
+          move = __any(!(z <= 0x1p64f));
+        }
+        if (move) {
+          float bm = fmaxf(a[0], a[1]);
+#pragma unroll
+          for (int v = 2; v < 16; v += 2) bm = fmaxf(fmaxf(bm, a[v]), a[v + 1]);
+          const float mn = fmaxf(m_run[q], bm * sc);
+          z_run[q] = (mn == -kInf) ? 0.f : z_run[q] * fast_exp2(m_run[q] - mn);
+          m_run[q] = mn;
+          const float mu = (mn == -kInf) ? 0.f : mn;
+          z = 0.f;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) z += fast_exp2(__builtin_fmaf(a[v], sc, -mu));
+        }
+        z_run[q] += z;
+        seeded |= 1u << q;
+      };
+      // Row blocks go through in pairs, one pair behind: while the matrix pipe works
+      // on the logits of pair i, the vector units take the exponentials of pair i - 1.
+      // In DOC kernels a pair none of whose rows sees the key block is left out (the
+      // limits grow with the row, and a wave's key blocks come in ascending order, so a
+      // row block that is left out once stays out).
+      auto process = [&](const bf16x8(&kf)[D / 16], int blk) {
+        const int kbase = blk << 5;
+        auto pair_visible = [&](int q) { return !DOC || kbase < lim_hi(q + 1 < QB ? q + 1 : q); };
+        f32x16 acc[QBT];
+#pragma unroll
+        for (int q = 0; q < QBT + 2; q += 2) {
+          if (q < QBT && q < QB && pair_visible(q)) {
+            if (q + 1 < QB) {
+              mfma_block_pair_lds<D>(kf, lds_q, q, lane, acc[q], acc[q + 1]);
+            } else {
+              bf16x8 qf0[D / 16];
+              load_q_frags<D>(lds_q, q, lane, qf0);
+              acc[q] = mfma_block<D>(kf, qf0);
+            }
+          }
+          if (q >= 2 && q - 2 < QB && pair_visible(q - 2)) {
+            tile_stats(acc[q - 2], q - 2, kbase);
+            if (q - 1 < QB) tile_stats(acc[q - 1], q - 1, kbase);
+          }
+        }
+      };
+      if (b < nbc) {
+        while (true) {
+          if (b + kOwnWaves < nbc) load_k_block<D>(ks, N, (b + kOwnWaves) << 5, lane, kb);
+          process(ka, b);
+          b += kOwnWaves;
+          if (b >= nbc) break;
+          if (b + kOwnWaves < nbc) load_k_block<D>(ks, N, (b + kOwnWaves) << 5, lane, ka);
+          process(kb, b);
+          b += kOwnWaves;
+          if (b >= nbc) break;
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < QBT; ++q) {
+        if (q < QB) {
+          float m = m_run[q], z = z_run[q];
+          const float m2 = __shfl_xor(m, 32);
+          const float z2 = __shfl_xor(z, 32);
+          merge_stats(m, z, m2, z2);
+          if (h == 0) wstats[wave * RC + q * 32 + t] = make_float2(m, z);
+        }
+      }
+    }
+
+    // ---- pass 2 walks the keys from the end (what pass 1 read last is what the
+    // caches most likely still hold); its first block is requested before the merge
+    b = nbc - 1 - wave;
+    if (b >= 0) load_k_block<D>(ks, N, b << 5, lane, ka);
+    if (tid == 0) *sh_next = kOwnWaves;
+    __syncthreads();
+    for (int i = tid; i < rows; i += kOwnThreads) {
+      float l = kInf;  // padding rows add exp2(-inf) = 0
+      if (row0 + i < R) {
+        float2 a = wstats[i];
+#pragma unroll
+        for (int w = 1; w < kOwnWaves; ++w) {
+          const float2 c = wstats[w * RC + i];
+          merge_stats(a.x, a.y, c.x, c.y);
+        }
+        l = a.x + fast_log2(a.y);
+        if (lim_step == 0) {
+          if (pb.lse_extra) l = widen_lse(l, as_global<float>(pb.lse_extra)[row0 + i]);
+        } else {
+          // normalisation step: the row's weights times (keys it sees) / (c + m)
+          l -= fast_log2(static_cast<float>(lim0 + i) / static_cast<float>(N));
+        }
+      }
+      lds_lse[i] = l;
+    }
+    __syncthreads();
+    {
+      auto process = [&](const bf16x8(&kf)[D / 16], int blk) {
+        const int kbase = blk << 5;
+        float u[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) u[v] = 0.f;
+        auto tile_sums = [&](f32x16 a, int q) {
+          const float L = lds_lse[q * 32 + t];
+          if (DOC && kbase + 32 > lim_lo(q)) {  // keys this row does not see add nothing
+            const int lim = lim_mine(q);
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+              if (kbase + acc_key(v, h) >= lim) a[v] = -kInf;
+          }
+#pragma unroll
+          for (int v = 0; v < 16; ++v) u[v] += fast_exp2(__builtin_fmaf(a[v], sc, -L));
+        };
+        auto pair_visible = [&](int q) { return !DOC || kbase < lim_hi(q + 1 < QB ? q + 1 : q); };
+        // pairs of row blocks, the vector work one pair behind the matrix work
+        f32x16 acc[QBT];
+#pragma unroll
+        for (int q = 0; q < QBT + 2; q += 2) {
+          if (q < QBT && q < QB && pair_visible(q)) {
+            if (q + 1 < QB) {
+              mfma_block_pair_lds<D>(kf, lds_q, q, lane, acc[q], acc[q + 1]);
+            } else {
+              bf16x8 qf0[D / 16];
+              load_q_frags<D>(lds_q, q, lane, qf0);
+              acc[q] = mfma_block<D>(kf, qf0);
+            }
+          }
+          if (q >= 2 && q - 2 < QB && pair_visible(q - 2)) {
+            tile_sums(acc[q - 2], q - 2);
+            if (q - 1 < QB) tile_sums(acc[q - 1], q - 1);
+          }
+        }
+        const float tot = fold16_over32(u, t);
+        const int key = kbase + acc_key(t >> 1, h);
+        if ((t & 1) == 0 && key < N) dst[key] = first_chunk ? tot : dst[key] + tot;
+      };
+      if (b >= 0) {
+        while (true) {
+          int bn = nbc - 1 - own_next_block(sh_next, lane);
+          if (bn >= 0) load_k_block<D>(ks, N, bn << 5, lane, kb);
+          process(ka, b);
+          b = bn;
+          if (b < 0) break;
+          bn = nbc - 1 - own_next_block(sh_next, lane);
+          if (bn >= 0) load_k_block<D>(ks, N, bn << 5, lane, ka);
+          process(kb, b);
+          b = bn;
+          if (b < 0) break;
+        }
+      }
+    }
+    __syncthreads();  // scores of this row chunk are out; LDS may be restaged
+  }
+  // what the prompt-row region of LDS holds now (selection scratch lies behind it)
+  staged_q = (n_chunks == 1) ? pb.q : nullptr;
+  staged_rows = Rp;
+  if (!stages) return;
+
+  // ---- top-r on the scores this workgroup has just written
+  const int r = min(pb.r, N);
+  if (r <= 0) return;
+  FINCH_GLOBAL int* gidx = as_global_mut<int>(pb.idx);
+  const bool identity = r >= N;
+  // selection scratch: behind the staged prompt rows (pass-1 statistics are dead)
+  char* sel = smem + RC * kStride;
+  const size_t sel_bytes = prm.lds_bytes - static_cast<size_t>(RC) * kStride;
+  SelLds* fl = reinterpret_cast<SelLds*>(sel);
+  int* lidx = nullptr;
+  if (identity) {
+    for (int i = tid; i < N; i += kOwnThreads) gidx[i] = i;
+  } else {
+    size_t used = sizeof(SelLds);
+    if (used + static_cast<size_t>(r) * 4 <= sel_bytes) {
+      lidx = reinterpret_cast<int*>(sel + used);
+      used += static_cast<size_t>(r) * 4;
+    }
+    if (N <= kOwnThreads * kSelRegKeys) {
+      select_regs<kOwnThreads>(dst, N, r, gidx, lidx, fl, tid, lane, wave);
+    } else {
+      unsigned* lkeys = nullptr;
+      if (used + static_cast<size_t>(N) * 4 <= sel_bytes) {
+        lkeys = reinterpret_cast<unsigned*>(sel + used);
+        for (int i = tid; i < N; i += kOwnThreads) lkeys[i] = order_key(dst[i]);
+      }
+      __syncthreads();
+      select_generic<kOwnThreads>(lkeys, dst, N, r, gidx, lidx, fl, tid, lane, wave);
+    }
+    __syncthreads();  // idx (LDS and memory) complete
+  }
+
+  // ---- compaction
+  if (ROT) {
+    own_gather_rot<D / 8>(pb, N, r, lidx, gidx, identity, prm.rope_pairing, prm.rope_log2_base, tid);
+  } else {
+    own_gather<D / 8>(pb, N, r, lidx, gidx, identity, tid);
+  }
+}
+
+// One launch = one step of every problem of a batch; workgroup b owns problem b.
+// ROT: the compaction re-positions the kept keys (prm.rope_pairing, ascending slots).
+template <int D, int QBT, bool ROT, bool DOC>
+__global__ __launch_bounds__(kOwnThreads) void owner_step_bf16(LaunchParams prm, int stages) {
+  extern __shared__ __align__(16) char smem[];
+  const int p = blockIdx.x;
+  const finch_problem pb = prm.probs[p];
+  const void* staged_q = nullptr;
+  int staged_rows = 0;
+  own_step_body<D, QBT, ROT, DOC>(prm, pb, p, stages, smem, staged_q, staged_rows);
+}
+
+// One launch = the whole chunk loop (Method: Document Segmentation): workgroup b
+// owns slot b and runs its steps one after the other; the descriptors of step s
+// are prm.probs[step_first[s] + slot] for slot < step_first[s+1] - step_first[s].
+// Slots do not depend on each other, so workgroups drift apart and the copy-bound
+// and arithmetic-bound stages of different problems overlap.
+template <int D, int QBT, bool ROT, bool DOC>
+__global__ __launch_bounds__(kOwnThreads) void owner_loop_bf16(LaunchParams prm, const int* step_first,
+                                                               int n_steps) {
+  extern __shared__ __align__(16) char smem[];
+  const int slot = blockIdx.x;
+  const void* staged_q = nullptr;
+  int staged_rows = 0;
+  for (int s = 0; s < n_steps; ++s) {
+    const int first = step_first[s];
+    if (slot >= step_first[s + 1] - first) break;  // slots are filled from the front
+    const finch_problem pb = prm.probs[first + slot];
+    own_step_body<D, QBT, ROT, DOC>(prm, pb, slot, /*stages=*/1, smem, staged_q, staged_rows);
+    // the rows this step wrote are the next step's cache: complete before it reads
+    __syncthreads();
+  }
+}
+
+namespace {
+
+int own_qbt(int row_chunk) {
+  const int qb = (row_chunk + 31) / 32;
+  const int have[4] = {2, 4, 6, 8};
+  for (int i = 0; i < 4; ++i)
+    if (qb <= have[i]) return have[i];
+  return 0;
+}
+
+// Calls f(kernel) for the instantiation that matches (head_dim, qbt, rot); `loop`
+// picks the whole-loop kernel.  Returns false for a combination that is not built.
+template <bool DOC, typename F>
+bool with_step_kernel(int head_dim, int qbt, bool rot, F f) {
+#define FINCH_OWN_CASE(DD, QQ)                                           \
+  if (head_dim == DD && qbt == QQ) {                                     \
+    if (rot) f(&owner_step_bf16<DD, QQ, true, DOC>);                     \
+    else f(&owner_step_bf16<DD, QQ, false, DOC>);                        \
+    return true;                                                         \
+  }
+  FINCH_OWN_CASE(128, 2) FINCH_OWN_CASE(128, 4) FINCH_OWN_CASE(128, 6) FINCH_OWN_CASE(128, 8)
+  FINCH_OWN_CASE(64, 2) FINCH_OWN_CASE(64, 4) FINCH_OWN_CASE(64, 6) FINCH_OWN_CASE(64, 8)
+#undef FINCH_OWN_CASE
+  return false;
+}
+template <bool DOC, typename F>
+bool with_loop_kernel(int head_dim, int qbt, bool rot, F f) {
+#define FINCH_OWN_CASE(DD, QQ)                                           \
+  if (head_dim == DD && qbt == QQ) {                                     \
+    if (rot) f(&owner_loop_bf16<DD, QQ, true, DOC>);                     \
+    else f(&owner_loop_bf16<DD, QQ, false, DOC>);                        \
+    return true;                                                         \
+  }
+  FINCH_OWN_CASE(128, 2) FINCH_OWN_CASE(128, 4) FINCH_OWN_CASE(128, 6) FINCH_OWN_CASE(128, 8)
+  FINCH_OWN_CASE(64, 2) FINCH_OWN_CASE(64, 4) FINCH_OWN_CASE(64, 6) FINCH_OWN_CASE(64, 8)
+#undef FINCH_OWN_CASE
+  return false;
+}
+
+// p.row_chunk and p.lds_bytes must describe this kernel's layout (owner_lds_bytes).
+template <bool DOC>
+hipError_t launch_owner_impl(int head_dim, const LaunchParams& p, int stages, hipStream_t s) {
+  if (p.n_problems <= 0) return hipSuccess;
+  const dim3 grid(static_cast<unsigned>(p.n_problems)), block(kOwnThreads);
+  const bool ok = with_step_kernel<DOC>(head_dim, own_qbt(p.row_chunk), p.rope_pairing != FINCH_ROPE_OFF,
+                                        [&](auto kern) {
+                                          hipLaunchKernelGGL(kern, grid, block, p.lds_bytes, s, p, stages);
+                                        });
+  return ok ? hipGetLastError() : hipErrorInvalidValue;
+}
+
+// The whole loop: n_slots workgroups; step_first is a DEVICE array of n_steps + 1
+// offsets into p.probs.
+template <bool DOC>
+hipError_t launch_owner_loop_impl(int head_dim, const LaunchParams& p, const int* step_first, int n_steps,
+                                  int n_slots, hipStream_t s) {
+  if (n_slots <= 0 || n_steps <= 0) return hipSuccess;
+  const dim3 grid(static_cast<unsigned>(n_slots)), block(kOwnThreads);
+  const bool ok = with_loop_kernel<DOC>(head_dim, own_qbt(p.row_chunk), p.rope_pairing != FINCH_ROPE_OFF,
+                                        [&](auto kern) {
+                                          hipLaunchKernelGGL(kern, grid, block, p.lds_bytes, s, p, step_first,
+                                                             n_steps);
+                                        });
+  return ok ? hipGetLastError() : hipErrorInvalidValue;
+}
+
+template <bool DOC>
+hipError_t set_max_lds_owner_impl(size_t bytes) {
+  hipError_t err = hipSuccess;
+  const int dims[2] = {128, 64}, qbts[4] = {2, 4, 6, 8};
+  for (int d = 0; d < 2; ++d)
+    for (int q = 0; q < 4; ++q)
+      for (int rot = 0; rot < 2; ++rot) {
+        auto set = [&](auto kern) {
+          const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                   static_cast<int>(bytes));
+          if (e != hipSuccess) err = e;
+        };
+        with_step_kernel<DOC>(dims[d], qbts[q], rot != 0, set);
+        with_loop_kernel<DOC>(dims[d], qbts[q], rot != 0, set);
+      }
+  return err;
+}
+
+}  // namespace
+
+}  // namespace finch

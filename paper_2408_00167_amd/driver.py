@@ -26,6 +26,8 @@ class ChunkLoop:
         K, V    [n_cont][d] document keys / values (device tensors)
         n_que   prompt rows per query head (R = group * n_que)
         budget  k, rows to keep at the end
+        Q_doc   optional: [G][chunk][d] queries of a chunk's own tokens (or a list, one
+                per step): scoring then also takes those rows, under the causal mask
         K_que   optional: [n_que][d] the prompt's own keys (or a list, one per step):
                 the softmax denominators then include them (finch_prompt_lse runs
                 at the start of `run`)
@@ -88,6 +90,7 @@ class ChunkLoop:
             self.row_off.append(self.row_off[-1] + int(q0.shape[0]))
         self.lse_extra = (torch.zeros(self.n_steps if self.per_step_prompt else 1, max(1, self.row_off[-1]),
                                       dtype=torch.float32, device=dev) if self.exact else None)
+        self._keep: List[torch.Tensor] = []      # tensors the descriptors point into
         self.batches: List[Batch] = []
         self.active: List[List[int]] = []
         self.step_shapes: List[List[tuple]] = []
@@ -111,12 +114,20 @@ class ChunkLoop:
                 q = pb["Q"][i] if isinstance(pb["Q"], (list, tuple)) else pb["Q"]
                 kq = pb.get("K_que")
                 kq = kq[i] if isinstance(kq, (list, tuple)) else kq
+                qd = pb.get("Q_doc")
+                qd = qd[i] if isinstance(qd, (list, tuple)) else qd
+                if qd is not None:
+                    # [G][chunk][d] -> the [G * m][d] block of this step (a copy if the chunk is short)
+                    qd = qd[:, :hi - lo].reshape(-1, qd.shape[-1])
+                    if not qd.is_contiguous():
+                        qd = qd.contiguous()
+                    self._keep.append(qd)
                 extra = None
                 if kq is not None:
                     extra = self.lse_extra[i if self.per_step_prompt else 0,
                                            self.row_off[p]:self.row_off[p + 1]]
                 descs.append(dict(
-                    q=q, k_que=kq, lse_extra=extra,
+                    q=q, k_que=kq, lse_extra=extra, q_doc=qd,
                     k_cache=self.kbuf[src][o:o + c], v_cache=self.vbuf[src][o:o + c],
                     k_chunk=pb["K"][lo:hi], v_chunk=pb["V"][lo:hi],
                     k_out=self.kbuf[dst][o:o + max(r, 1)], v_out=self.vbuf[dst][o:o + max(r, 1)],

@@ -97,7 +97,15 @@ def validate_chunk_loop(loop: ChunkLoop, check: Sequence[int], what: str = "") -
                                        loop.row_off[p]:loop.row_off[p + 1]].double().cpu().numpy()
                 ref = O.prompt_lse(W.to_numpy_storage(q), W.to_numpy_storage(kq), q.shape[0] // pb["n_que"])
                 assert np.abs(extra - ref).max() < 1e-5 * max(1.0, np.abs(ref).max()), f"{what}: lse_extra"
-            want_scores = O.key_scores(W.to_numpy_storage(q), Kc, Kd[lo:hi], lse_extra=extra)
+            qd = pb.get("Q_doc")
+            qd = qd[i] if isinstance(qd, (list, tuple)) else qd
+            if qd is not None:
+                G = qd.shape[0]
+                qd_step = W.to_numpy_storage(qd[:, :hi - lo].reshape(-1, qd.shape[-1]).contiguous())
+                want_scores = O.key_scores_conditioned(W.to_numpy_storage(q), qd_step, Kc, Kd[lo:hi], G,
+                                                       lse_extra=extra)
+            else:
+                want_scores = O.key_scores(W.to_numpy_storage(q), Kc, Kd[lo:hi], lse_extra=extra)
             g_scores, g_idx = loop.step_outputs(i, p)
             g_scores, g_idx = g_scores.cpu().numpy(), g_idx.cpu().numpy()
             tag = f"{what} problem {pb.get('id', p)} step {i}"
@@ -141,6 +149,12 @@ def single_step_case(fin: F.Finch, specs: Sequence[Dict], dtype: torch.dtype, d:
             scores=None if null_scores else torch.full((max(N, 1) + 1,), -5.0, device="cuda"),
             idx=torch.full((max(rr, 1) + 1,), -9, dtype=torch.int32, device="cuda"),
             n_que=sp["n_que"], c=c, m=m, r=r)
+        t["group"] = group
+        if sp.get("doc_rows"):
+            # queries of the chunk's own tokens, head by head
+            t["q_doc"] = rand_storage((group * m, d), dtype, gen, sp.get("qscale", 1.0)) if m > 0 else None
+            if sp.get("no_prompt"):
+                t["q"] = None
         if sp.get("prompt_keys"):
             # the prompt's own keys and room for the per-row term they add to the denominator
             t["k_que"] = rand_storage((sp["n_que"], d), dtype, gen, sp.get("qscale", 1.0))
@@ -192,7 +206,7 @@ def validate_single_step(ts: Sequence[Dict], what: str, check_scores_too: bool =
     torch.cuda.synchronize()
     stats = dict(swaps=0, worst_rel=0.0, worst_rot=0.0)
     for n, t in enumerate(ts):
-        tol = SCORE_TOL[dtype_name(t["q"])]
+        tol = SCORE_TOL[dtype_name(t["k_out"])]
         N, r = t["c"] + t["m"], t["r"]
         rr = min(r, N)
         Kc, Kk = W.to_numpy_storage(t["k_cache"]), W.to_numpy_storage(t["k_chunk"])
@@ -202,7 +216,13 @@ def validate_single_step(ts: Sequence[Dict], what: str, check_scores_too: bool =
             # the scoring is checked with the term the GPU was given (itself checked apart)
             extra = t["lse_extra"][:-1].double().cpu().numpy()
             assert float(t["lse_extra"][-1]) == -77.0, "wrote past the end of lse_extra"
-        want = O.key_scores(W.to_numpy_storage(t["q"]), Kc, Kk, lse_extra=extra)
+        if t.get("q_doc") is not None or t["q"] is None:
+            want = O.key_scores_conditioned(
+                None if t["q"] is None else W.to_numpy_storage(t["q"]),
+                None if t.get("q_doc") is None else W.to_numpy_storage(t["q_doc"]), Kc, Kk, t["group"],
+                lse_extra=extra)
+        else:
+            want = O.key_scores(W.to_numpy_storage(t["q"]), Kc, Kk, lse_extra=extra)
         tag = f"{what} problem {n} (n_que={t['n_que']}, c={t['c']}, m={t['m']}, r={r})"
         if check_scores_too and t["scores"] is not None:
             got = t["scores"].cpu().numpy()

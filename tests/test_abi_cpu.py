@@ -29,7 +29,7 @@ def test_library_exports_every_declared_function():
 
 
 def test_problem_struct_layout_matches_header():
-    assert ctypes.sizeof(F.finch_problem) == 104
+    assert ctypes.sizeof(F.finch_problem) == 112
     assert F.finch_problem.n_que.offset == 72 and F.finch_problem.r.offset == 84
     assert ctypes.sizeof(F.finch_config) == 16
 

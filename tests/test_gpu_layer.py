@@ -37,7 +37,7 @@ def validate_layers(ts, L, what):
         for t in heads:
             want = O.key_scores(W.to_numpy_storage(t["q"]), W.to_numpy_storage(t["k_cache"]),
                                 W.to_numpy_storage(t["k_chunk"]))
-            H.check_scores(t["scores"].cpu().numpy()[:N], want, H.SCORE_TOL[H.dtype_name(t["q"])], f"{what} run {run}")
+            H.check_scores(t["scores"].cpu().numpy()[:N], want, H.SCORE_TOL[H.dtype_name(t["k_out"])], f"{what} run {run}")
             per_head.append(want)
         total = O.layer_scores(per_head)
         idx = t0["idx"].cpu().numpy()
