@@ -21,9 +21,8 @@
  * Threads: a context holds only settings (set_option, set_reposition, profile) and
  * the last HIP error; with finch_profile off, calls that do not change settings may
  * run from several host threads on the same context as long as each call has its
- * own workspace.  Calls
- * that share a workspace, or descriptors whose outputs overlap, must be ordered by
- * the caller (same stream, or events).
+ * own workspace.  Calls that share a workspace, or descriptors whose outputs
+ * overlap, must be ordered by the caller (same stream, or events).
  *
  * Errors: every function returns a finch_status.  Argument errors are detected on
  * the host before anything is launched.  Non-finite inputs are undefined
