@@ -67,3 +67,40 @@ def test_random_shapes(seed, options):
         fin.close()
         problems += len(specs)
     say(f"seed {seed}: {problems} problems")
+
+
+@pytest.mark.parametrize("seed", [21, 22])
+def test_random_chunk_loops(seed):
+    """Whole chunk loops with random document lengths, chunk sizes, prompt lengths and
+    budgets (so that the cache grows through several key blocks and the slots drop out
+    at different steps), as one launch and step by step, every step against the oracle."""
+    import workloads as W
+    from paper_2408_00167_amd.driver import ChunkLoop
+    rng = np.random.default_rng(seed)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    for trial in range(3):
+        d = int(rng.choice([64, 128]))
+        group = int(rng.choice([1, 4]))
+        chunk = int(rng.choice([96, 256, 700]))
+        fin = F.Finch(F.FINCH_BF16, d, group)
+        fin.set_step_path([F.FINCH_PATH_AUTO, F.FINCH_PATH_OWNER, F.FINCH_PATH_SEPARATE][trial])
+        probs = []
+        for j in range(int(rng.integers(2, 6))):
+            n = int(rng.integers(chunk // 2, 9 * chunk))
+            n_que = int(rng.integers(1, 50))
+            probs.append(dict(Q=H.rand_storage((group * n_que, d), torch.bfloat16, gen),
+                              K=H.rand_storage((n, d), torch.bfloat16, gen),
+                              V=H.rand_storage((n, d), torch.bfloat16, gen),
+                              n_que=n_que, budget=int(rng.integers(1, max(2, n // 2))), id=j))
+        say(f"seed {seed} trial {trial}: d={d} G={group} chunk={chunk} "
+            f"lengths={[int(p['K'].shape[0]) for p in probs]} budgets={[p['budget'] for p in probs]}")
+        outs = []
+        for per_step in (False, True):
+            loop = ChunkLoop(fin, probs, chunk, history=True)
+            loop.run(per_step=per_step)
+            st = H.validate_chunk_loop(loop, list(range(len(probs))), f"sweep loop per_step={per_step}")
+            say(f"   per_step={per_step}: {st}")
+            outs.append(loop)
+        assert torch.equal(outs[0].idx, outs[1].idx)
+        fin.close()
