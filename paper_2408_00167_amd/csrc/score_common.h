@@ -208,36 +208,49 @@ __device__ __forceinline__ void mfma_block_pair_lds(const bf16x8 (&kf)[D / 16], 
   }
 }
 
+// A value of the lane that a DPP control names (row_ror:8 = lane ^ 8, row_half_mirror =
+// lane ^ 7, quad_perm [2,3,0,1] = lane ^ 2, quad_perm [1,0,3,2] = lane ^ 1).
+template <int CTRL>
+__device__ __forceinline__ float from_lane_dpp(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, true));
+}
+
 // Sum each of 16 per-lane values over the 32 lanes of a lane-half.  On return the
 // lane with in-half index t holds the total of value index t >> 1.  Fixed order.
+// Five halving rounds: a lane keeps the half of its values that its own lane bit
+// selects and adds the partner's sums of the same values.  The partners are lane ^ 16
+// (one permlane16_swap per pair of values: the odd 16-lane rows of the first change
+// places with the even rows of the second, after which the two registers hold exactly
+// the two addends), then lane ^ 8, lane ^ 7, lane ^ 2, lane ^ 1 through DPP - no trip
+// through the LDS crossbar, which the matrix operands keep busy.  (Any partner with the
+// same higher bits and the opposite bit of the round will do: lane ^ 7 is what a
+// single DPP control offers for the third round.)
 __device__ __forceinline__ float fold16_over32(const float (&u)[16], int t) {
   float w8[8], w4[4], w2[2];
-  const bool b4 = (t & 16) != 0;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const float keep = b4 ? u[i + 8] : u[i];
-    const float send = b4 ? u[i] : u[i + 8];
-    w8[i] = keep + __shfl_xor(send, 16);
+    const auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(u[i]), __float_as_uint(u[i + 8]), false, false);
+    w8[i] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
   }
   const bool b3 = (t & 8) != 0;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const float keep = b3 ? w8[i + 4] : w8[i];
     const float send = b3 ? w8[i] : w8[i + 4];
-    w4[i] = keep + __shfl_xor(send, 8);
+    w4[i] = keep + from_lane_dpp<0x128>(send);
   }
   const bool b2 = (t & 4) != 0;
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const float keep = b2 ? w4[i + 2] : w4[i];
     const float send = b2 ? w4[i] : w4[i + 2];
-    w2[i] = keep + __shfl_xor(send, 4);
+    w2[i] = keep + from_lane_dpp<0x141>(send);
   }
   const bool b1 = (t & 2) != 0;
   const float keep = b1 ? w2[1] : w2[0];
   const float send = b1 ? w2[0] : w2[1];
-  float w1 = keep + __shfl_xor(send, 2);
-  w1 += __shfl_xor(w1, 1);
+  float w1 = keep + from_lane_dpp<0x4E>(send);
+  w1 += from_lane_dpp<0xB1>(w1);
   return w1;
 }
 
