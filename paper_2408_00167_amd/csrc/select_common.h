@@ -24,6 +24,20 @@ __device__ __forceinline__ unsigned order_key(float f) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave without a trip through LDS: shifts
+// by 1, 2, 4, 8 inside each row of 16 lanes (zeros shifted in), then lane 15 of every
+// even row is added to the row above it and lane 31 to the upper half.
+__device__ __forceinline__ int wave_inclusive_scan(int x) {
+  int v = x;
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, true);   // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, true);   // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, true);   // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, true);   // row_shr:8
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false);  // row_bcast:15 into rows 1, 3
+  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);  // row_bcast:31 into rows 2, 3
+  return v;
+}
+
 struct SelLds {  // LDS scratch of a selection
   int hist[4][256];
   int wave_tot[2][kSelMaxWaves];
@@ -36,12 +50,9 @@ __device__ __forceinline__ void sel_pick_digit(const int* hist, int remaining, i
                                                int* left_out) {
   const int h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
   const int mine = h0 + h1 + h2 + h3;
-  int suffix = mine;  // inclusive sum over lanes >= this one
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int x = __shfl_down(suffix, o);
-    if (lane + o < 64) suffix += x;
-  }
+  const int prefix = wave_inclusive_scan(mine);
+  const int total = __builtin_amdgcn_readlane(prefix, 63);
+  const int suffix = total - prefix + mine;  // inclusive sum over lanes >= this one
   const int above = suffix - mine;  // keys in bins of higher lanes
   if (above < remaining && remaining <= suffix) {
     int left = remaining - above;  // >= 1
@@ -87,12 +98,7 @@ __device__ __forceinline__ int sel_block_rank(bool flag, int* wave_tot, int lane
 // barrier; `wave_tot` must not be reused before another barrier.
 template <int NT>
 __device__ __forceinline__ int sel_block_scan(int v, int* wave_tot, int lane, int wave) {
-  int incl = v;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int x = __shfl_up(incl, o);
-    if (lane >= o) incl += x;
-  }
+  const int incl = wave_inclusive_scan(v);
   if (lane == 63) wave_tot[wave] = incl;
   __syncthreads();
   int base = 0;
