@@ -144,7 +144,12 @@ __device__ __forceinline__ void own_step_body(const LaunchParams& prm, const fin
   const int N = pb.c + pb.m;
   if (N == 0) return;
   const int Rp = (DOC && !pb.q) ? 0 : prm.group * pb.n_que;  // prompt rows
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // (the thread index goes through an empty asm: in the whole-loop kernel the compiler
+  // would otherwise compute everything that depends only on it once for all steps and
+  // keep it in registers through every phase)
+  int tid_ = threadIdx.x;
+  asm volatile("" : "+v"(tid_));
+  const int tid = tid_, lane = tid & 63, wave = tid >> 6;
   const int t = lane & 31, h = lane >> 5;
   constexpr int kStride = D * 2 + 16;
   const int RC = prm.row_chunk;
