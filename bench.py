@@ -22,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
 COPY_CALIBRATION_BYTES = 1 << 30
 
 # HBM bytes per launch from hardware counters (two rocprofv3 --pmc runs of this
@@ -54,6 +55,17 @@ def algorithmic_bytes(w, loop):
             per["gather"] += min(r, N) * d * e * 4
     total = per["score_pass"] + per["gather"]
     return per, total, keys
+
+
+def logit_flops(w, loop):
+    """Multiply-adds x 2 of the logits the method forms: every (prompt row, candidate key)
+    pair once per scoring pass, two passes (document rows, when they are on, not counted)."""
+    flops = 0
+    for i in range(loop.n_steps):
+        for p, (c, m, r) in zip(loop.active[i], loop.step_shapes[i]):
+            R = w.group * loop.problems[p]["n_que"]
+            flops += 2 * 2 * (c + m) * R * w.head_dim
+    return flops
 
 
 def cpu_baseline(w, next_problem, chunk, budget_s=15.0):
@@ -215,6 +227,13 @@ def main() -> int:
                         bytes_per_launch=bytes_per_launch, avg_launch_us=kernels[dom]["avg_us"],
                         launches_per_step=launches, profiled_ms_per_step=prof_ms)
 
+    # what the arithmetic side of the same launches amounts to (bf16 runs; information
+    # beside the contract's HBM figure: the scoring passes are not bound by memory)
+    matrix_pipe = None
+    if w.dtype == "bf16" and not args.doc_rows:
+        fl = logit_flops(w, loop)
+        matrix_pipe = dict(logit_flops=fl, achieved_TFLOPs=fl / (ms * 1e-3) / 1e12, peak_TFLOPs=MFMA_BF16_PEAK_TFLOPS,
+                           frac=fl / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS)
     path_gbps = total_bytes / (ms * 1e-3) / 1e9
     out = {
         "metric": "document tokens compressed/sec (score+topk+compact); achieved HBM GB/s",
@@ -238,6 +257,7 @@ def main() -> int:
                  "frac_of_hbm_peak": path_gbps / HBM_PEAK_GBPS},
         "kernels": kernels,
         "roofline": roofline,
+        "matrix_pipe": matrix_pipe,
         "setup_s": t_gen,
     }
     if not args.no_cpu_baseline:
