@@ -176,6 +176,21 @@ finch_status finch_step(finch_ctx* ctx, const finch_problem* host_desc,
                         const finch_problem* dev_desc, int32_t n_problems,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/* finch_step for callers that cannot allocate and have no workspace to pass: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same
+ * step with the same results, but the scratch memory (row statistics, row
+ * log-sum-exps, scores of descriptors whose `scores` is NULL, layer sums) is a
+ * file-scope device array inside the library, finch_static_scratch_bytes() = 16 MiB on
+ * every GPU the library is used on, held until the process ends.  A batch that needs
+ * more (finch_workspace_size tells) is refused with FINCH_ERR_CAPACITY and a message on
+ * stderr; nothing is launched then.  The call allocates nothing and frees nothing.
+ * All calls on one GPU share that GPU's array, which keeps the last call's contents
+ * (nothing in it has to start at zero): calls that overlap in time on one GPU - two
+ * streams, two contexts, two threads - race; order them on one stream or with events. */
+finch_status finch_step_static(finch_ctx* ctx, const finch_problem* host_desc,
+                               const finch_problem* dev_desc, int32_t n_problems, void* stream);
+size_t finch_static_scratch_bytes(void);
+
 /* The whole chunk loop in one call (Method: Document Segmentation - chunk after
  * chunk, each step's kept pairs competing with the next chunk): the same results as
  * finch_step on the batch of step 0, then on that of step 1, and so on.  The

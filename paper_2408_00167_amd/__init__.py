@@ -31,6 +31,7 @@ EXPORTED_SYMBOLS = (
     "finch_compact", "finch_step", "finch_schedule", "finch_schedule_mode", "finch_last_hip_error",
     "finch_status_string", "finch_version", "finch_profile", "finch_profile_read",
     "finch_set_option", "finch_set_reposition", "finch_prompt_lse", "finch_loop", "finch_loop_workspace_size",
+    "finch_step_static", "finch_static_scratch_bytes",
 )
 
 KERNEL_NAMES = ("rowstats", "lse", "colsum", "select", "gather", "owner", "prompt_lse")
@@ -116,6 +117,10 @@ def load_library() -> ctypes.CDLL:
     lib.finch_prompt_lse.restype = ctypes.c_int
     lib.finch_set_reposition.argtypes = [vp, P(finch_reposition)]
     lib.finch_set_reposition.restype = ctypes.c_int
+    lib.finch_step_static.argtypes = [vp, P(finch_problem), vp, i32, vp]
+    lib.finch_step_static.restype = ctypes.c_int
+    lib.finch_static_scratch_bytes.argtypes = []
+    lib.finch_static_scratch_bytes.restype = sz
     lib.finch_set_option.argtypes = [vp, i32, i64]
     lib.finch_set_option.restype = ctypes.c_int
     lib.finch_version.argtypes = []
@@ -180,6 +185,15 @@ def finch_compact(ctx, host_desc, dev_desc_ptr, n, ws_ptr, ws_bytes, stream=0):
 
 def finch_step(ctx, host_desc, dev_desc_ptr, n, ws_ptr, ws_bytes, stream=0):
     _call("finch_step", ctx, host_desc, dev_desc_ptr, n, ws_ptr, ws_bytes, stream)
+
+
+def finch_step_static(ctx, host_desc, dev_desc_ptr, n, stream=0):
+    _check(load_library().finch_step_static(ctx, host_desc, ctypes.c_void_p(dev_desc_ptr), n,
+                                            ctypes.c_void_p(stream)), "finch_step_static", ctx)
+
+
+def finch_static_scratch_bytes() -> int:
+    return int(load_library().finch_static_scratch_bytes())
 
 
 def finch_schedule(n_cont: int, m: int, k: int, constant_budget: bool = False) -> List[int]:
@@ -346,6 +360,12 @@ class Finch:
 
     def step(self, batch: Batch, stream=None):
         self._run("finch_step", batch, stream)
+
+    def step_static(self, batch: Batch, stream=None):
+        """finch_step on the library's own scratch: no workspace, nothing allocated."""
+        import torch
+        s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
+        finch_step_static(self.ctx, batch.host, batch.dev_ptr, batch.n, s)
 
     def prompt_lse(self, batch: Batch, stream=None):
         import torch

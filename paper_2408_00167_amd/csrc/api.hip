@@ -5,6 +5,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "finch_internal.h"
@@ -25,7 +26,14 @@ struct finch_ctx {
   int slice_keys;        // target keys per workgroup slice of the bf16 scoring kernels
   finch_reposition repos;  // {OFF, ASCENDING}: plain copies
   int layer_group;         // > 1: runs of that many problems share one selection
+  void* static_scratch;    // this device's copy of the file-scope scratch array (finch_step_static)
 };
+
+// Scratch of finch_step_static: the workspace of a step, held by the library itself so
+// that the call neither takes a workspace nor allocates.  Every GPU the library runs on
+// holds its own copy of the array, at its own address, until the process ends.
+constexpr size_t kStaticScratchBytes = size_t{16} << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -228,6 +236,28 @@ finch_status hip_fail(finch_ctx* ctx, hipError_t e) {
   return FINCH_ERR_HIP;
 }
 
+// Device address of `scratch` on each GPU.  In host code the array's name only stands
+// for the symbol; the address kernels can use comes from hipGetSymbolAddress, asked once
+// per device with that device current.
+constexpr int kMaxDevices = 64;
+void* g_scratch_addr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+hipError_t static_scratch_address(int device, void** out) {
+  *out = nullptr;
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_addr[device]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_addr[device] = p;
+  }
+  *out = g_scratch_addr[device];
+  return hipSuccess;
+}
+
 constexpr int kProfPairs = 8192;
 
 // Brackets one kernel launch with two events on the launch stream when profiling
@@ -366,6 +396,24 @@ finch_status check_steps(const int32_t* first, int32_t n_steps, int32_t* n_desc,
   return FINCH_OK;
 }
 
+// One step with its launches sized by `pl` (finch_step and finch_step_static).
+finch_status step_planned(finch_ctx* ctx, const finch_problem* host_desc, const finch_problem* dev_desc,
+                          int32_t n, const Plan& pl, void* ws, size_t ws_bytes, void* stream) {
+  finch_status st;
+  if ((st = validate(ctx, host_desc, n, kNeedQK | kNeedIdx | kNeedGather)) != FINCH_OK) return st;
+  if ((st = check_layer_runs(ctx, host_desc, n)) != FINCH_OK) return st;
+  if ((st = check_workspace(pl, ws, ws_bytes)) != FINCH_OK) return st;
+  if (n == 0) return FINCH_OK;
+  const LaunchParams p = make_params(ctx, dev_desc, n, pl, ws);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (pl.tiles_max > 0 && owner_wanted(ctx, pl, n)) return run_owner(ctx, p, pl, /*stages=*/1, s);
+  if ((ctx->step_path == FINCH_PATH_OWNER || pl.has_doc) && pl.tiles_max > 0) return FINCH_ERR_UNSUPPORTED;
+  if ((st = run_score(ctx, p, pl, s)) != FINCH_OK) return st;
+  if (pl.r_max == 0) return FINCH_OK;
+  if ((st = run_select(ctx, p, pl, ws, s)) != FINCH_OK) return st;
+  return run_gather(ctx, p, pl.r_max, s);
+}
+
 }  // namespace
 
 extern "C" {
@@ -395,7 +443,9 @@ finch_status finch_create(const finch_config* cfg, finch_ctx** out) {
   ctx->repos.pairing = FINCH_ROPE_OFF;
   ctx->repos.order = FINCH_ORDER_ASCENDING;
   ctx->repos.base = 10000.0;
+  ctx->static_scratch = nullptr;
   hipError_t e = hipGetDevice(&ctx->device);
+  if (e == hipSuccess) e = static_scratch_address(ctx->device, &ctx->static_scratch);
   if (e == hipSuccess) {
     int v = 0;
     e = hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, ctx->device);
@@ -594,19 +644,29 @@ finch_status finch_step(finch_ctx* ctx, const finch_problem* host_desc,
   if (st != FINCH_OK) return st;
   Plan pl;
   if ((st = make_plan(ctx, host_desc, n, pl)) != FINCH_OK) return st;
-  if ((st = validate(ctx, host_desc, n, kNeedQK | kNeedIdx | kNeedGather)) != FINCH_OK) return st;
-  if ((st = check_layer_runs(ctx, host_desc, n)) != FINCH_OK) return st;
-  if ((st = check_workspace(pl, ws, ws_bytes)) != FINCH_OK) return st;
-  if (n == 0) return FINCH_OK;
-  const LaunchParams p = make_params(ctx, dev_desc, n, pl, ws);
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  if (pl.tiles_max > 0 && owner_wanted(ctx, pl, n)) return run_owner(ctx, p, pl, /*stages=*/1, s);
-  if ((ctx->step_path == FINCH_PATH_OWNER || pl.has_doc) && pl.tiles_max > 0) return FINCH_ERR_UNSUPPORTED;
-  if ((st = run_score(ctx, p, pl, s)) != FINCH_OK) return st;
-  if (pl.r_max == 0) return FINCH_OK;
-  if ((st = run_select(ctx, p, pl, ws, s)) != FINCH_OK) return st;
-  return run_gather(ctx, p, pl.r_max, s);
+  return step_planned(ctx, host_desc, dev_desc, n, pl, ws, ws_bytes, stream);
 }
+
+finch_status finch_step_static(finch_ctx* ctx, const finch_problem* host_desc,
+                               const finch_problem* dev_desc, int32_t n, void* stream) {
+  finch_status st = check_common(ctx, host_desc, dev_desc, n);
+  if (st != FINCH_OK) return st;
+  Plan pl;
+  if ((st = make_plan(ctx, host_desc, n, pl)) != FINCH_OK) return st;
+  if (pl.total > kStaticScratchBytes) {
+    std::fprintf(stderr,
+                 "finch_step_static: this batch needs %zu bytes of scratch, the library holds %zu; "
+                 "use finch_step with a workspace\n",
+                 pl.total, kStaticScratchBytes);
+    return FINCH_ERR_CAPACITY;
+  }
+  if (!ctx->static_scratch) return FINCH_ERR_WORKSPACE;
+  // No part of the scratch has to start at zero: each region (row statistics, row
+  // log-sum-exps, scores, layer sums) is written by the step before it is read.
+  return step_planned(ctx, host_desc, dev_desc, n, pl, ctx->static_scratch, kStaticScratchBytes, stream);
+}
+
+size_t finch_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 finch_status finch_loop_workspace_size(const finch_ctx* ctx, const finch_problem* host_desc,
                                        const int32_t* host_step_first, int32_t n_steps, size_t* bytes) {
