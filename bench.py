@@ -26,9 +26,15 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
 COPY_CALIBRATION_BYTES = 1 << 30
 
 # HBM bytes per launch from hardware counters (two rocprofv3 --pmc runs of this
-# program on C4, FETCH_SIZE then WRITE_SIZE, each scaled by what the same counter
-# reads for the 1 GiB elementwise copy of --copy-calibration).  Offline figures:
-# bench.py cannot read counters itself.  None = not measured for that kernel/workload.
+# program on C4 with default options, FETCH_SIZE then WRITE_SIZE, each scaled by what
+# the same counter reads for the 1 GiB elementwise copy of --copy-calibration).
+# Offline figures (bench.py cannot read counters itself), reported only for a run with
+# the options they were taken with, together with the summary they come from.
+TRAFFIC_SOURCE = {"owner": "profiles/owner_loop_bf16_C4_hbm_traffic.txt",
+                  "rowstats": "profiles/stage_kernels_bf16_C4_hbm_traffic.txt",
+                  "colsum": "profiles/stage_kernels_bf16_C4_hbm_traffic.txt",
+                  "select": "profiles/stage_kernels_bf16_C4_hbm_traffic.txt",
+                  "gather": "profiles/stage_kernels_bf16_C4_hbm_traffic.txt"}
 MEASURED_TRAFFIC = {"C4": {
     "rowstats": 2.0 * 159794.9 * 1024 + 1792.0 * 1024,
     "colsum": 2.0 * 159570.6 * 1024 + 5804.0 * 1024,
@@ -68,30 +74,52 @@ def logit_flops(w, loop):
     return flops
 
 
-def cpu_baseline(w, next_problem, chunk, budget_s=15.0):
-    """The oracle, as it stands, on the host cores: whole chunk loops of sampled
-    problems (drawn one at a time from `next_problem` until about `budget_s` seconds
-    of oracle time have been spent), extrapolated linearly to the whole job."""
+def cpu_baseline(w, next_problem, chunk, budget_s=10.0, seed=12345):
+    """The oracle, as it stands, on the host cores, in two legs: BLAS free to use every
+    core, then pinned to one thread.  Each leg runs whole chunk loops of problems drawn
+    from a seeded shuffle of the workload's problems until about `budget_s` seconds of
+    oracle time have been spent, and is extrapolated linearly to the whole job."""
+    import random
+
     from oracle import finch_oracle as O
+    host_cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    blas_threads = None
     try:
-        from threadpoolctl import threadpool_info
-        cores = max([int(x.get("num_threads", 1)) for x in threadpool_info()] + [1])
+        from threadpoolctl import threadpool_info, threadpool_limits
+        blas_threads = max([int(x.get("num_threads", 1)) for x in threadpool_info()] + [1])
     except Exception:
-        cores = 1
-    done, dt = 0, 0.0
-    while dt < budget_s and done < w.n_problems:
-        pb = next_problem(done)
-        if pb is None:
-            break
-        t0 = time.perf_counter()
-        O.compress(pb["Q"], pb["K"], pb["V"], chunk, pb["budget"])
-        dt += time.perf_counter() - t0
-        done += 1
+        threadpool_limits = None
+    order = list(range(w.n_problems))
+    random.Random(seed).shuffle(order)
     n_tokens = sum(r.n_cont for r in w.requests)
-    whole_job_s = dt / done * w.n_problems
-    return dict(value=n_tokens / whole_job_s, unit="document tokens/s", cores=cores, kind="oracle",
-                sample=(f"{done} of {w.n_problems} problems of {w.name} (in workload order), full "
-                        f"chunk loop each, {dt:.1f} s of oracle time, extrapolated linearly to all problems"))
+
+    def leg(first):
+        done, dt = 0, 0.0
+        while dt < budget_s and done < len(order):
+            pb = next_problem(order[(first + done) % len(order)])
+            if pb is None:
+                break
+            t0 = time.perf_counter()
+            O.compress(pb["Q"], pb["K"], pb["V"], chunk, pb["budget"])
+            dt += time.perf_counter() - t0
+            done += 1
+        return done, dt
+
+    done_all, dt_all = leg(0)
+    out = dict(value=n_tokens / (dt_all / done_all * w.n_problems), unit="document tokens/s", cores=host_cores,
+               blas_threads=blas_threads, kind="oracle")
+    sample = (f"all cores: {done_all} of {w.n_problems} problems of {w.name} (seeded shuffle, seed {seed}), full "
+              f"chunk loop each, {dt_all:.1f} s of oracle time, extrapolated linearly to all problems")
+    if threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            done_1, dt_1 = leg(done_all)
+        if done_1:
+            out["single_thread_value"] = n_tokens / (dt_1 / done_1 * w.n_problems)
+            sample += f"; one thread: the next {done_1} problems of the same shuffle (wrapping round), {dt_1:.1f} s"
+    else:
+        sample += "; one-thread leg skipped (threadpoolctl not importable: BLAS threads cannot be pinned)"
+    out["sample"] = sample
+    return out
 
 
 def main() -> int:
@@ -196,6 +224,8 @@ def main() -> int:
     # (on the launch stream).  Kept out of the pass that produced `value` because the
     # event records themselves lengthen the loop.
     roofline, kernels = None, None
+    default_options = (args.reposition == "off" and args.order == "ascending" and args.layer_group == 1
+                       and not args.constant_budget and not args.doc_rows and not args.exact_denominator)
     if not args.no_profile:
         F.finch_profile(fin.ctx, True)
         prof_steps = min(args.steps, max(1, 8192 // max(1, 5 * loop.n_steps)))
@@ -223,7 +253,8 @@ def main() -> int:
         achieved = bytes_per_launch / (kernels[dom]["avg_us"] * 1e-6) / 1e9
         roofline = dict(bound="hbm", kernel=dom, achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s",
                         frac=achieved / HBM_PEAK_GBPS,
-                        traffic=MEASURED_TRAFFIC.get(w.name, {}).get(dom),
+                        traffic=MEASURED_TRAFFIC.get(w.name, {}).get(dom) if default_options else None,
+                        traffic_source=TRAFFIC_SOURCE.get(dom) if default_options and w.name in MEASURED_TRAFFIC else None,
                         bytes_per_launch=bytes_per_launch, avg_launch_us=kernels[dom]["avg_us"],
                         launches_per_step=launches, profiled_ms_per_step=prof_ms)
 

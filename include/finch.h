@@ -18,11 +18,12 @@
  * synchronising; nothing is allocated after finch_create.  Outputs are valid once
  * the caller has synchronised the stream.  Results are bit-identical run to run.
  *
- * Threads: a context holds only settings (set_option, set_reposition, profile) and
- * the last HIP error; with finch_profile off, calls that do not change settings may
- * run from several host threads on the same context as long as each call has its
- * own workspace.  Calls that share a workspace, or descriptors whose outputs
- * overlap, must be ordered by the caller (same stream, or events).
+ * Threads and streams: one context is for one host thread and one stream at a time (it
+ * holds settings, the last HIP error, the profiling pool and the memo of finch_loop's
+ * checks, none of them synchronised).  Concurrent use - several host threads, or work in
+ * flight on several streams - takes one context per thread or stream, each with its own
+ * workspace.  Calls that share a workspace, or descriptors whose outputs overlap, must
+ * be ordered by the caller (same stream, or events).
  *
  * Errors: every function returns a finch_status.  Argument errors are detected on
  * the host before anything is launched.  Non-finite inputs are undefined
@@ -214,6 +215,16 @@ finch_status finch_loop(finch_ctx* ctx, const finch_problem* host_desc,
                         const int32_t* dev_step_first, int32_t n_steps, void* workspace,
                         size_t workspace_bytes, void* stream);
 
+/* Host-only: the argument checks of finch_loop on a descriptor set, without a context
+ * and without touching a GPU (the pointers are only compared, never followed): step
+ * table, pointers and alignment, outputs that overlap their own sources, and the rule
+ * above that no slot may write memory another slot reads or writes
+ * (FINCH_ERR_INVALID_ARG).  finch_loop makes the same checks itself; the one on
+ * overlaps between slots it repeats only when the descriptors have changed since the
+ * last call on the context. */
+finch_status finch_loop_check(const finch_config* cfg, const finch_problem* host_desc,
+                              const int32_t* host_step_first, int32_t n_steps);
+
 /* Host-only: rows kept after each chunk step (Method: the update rule
  * r_{it+1} = m_{it+1}/sigma + c_it with sigma = n_cont/k, ending at r = k), in
  * integers: r_i = min(c_{i-1} + m_i, floor(min(k, n_cont) * seen_i / n_cont)).
@@ -233,8 +244,7 @@ finch_status finch_schedule_mode(int64_t n_cont, int32_t m, int64_t k, int32_t m
  * stages of the step - or, in finch_loop, of all steps - back to back with nothing
  * exchanged between workgroups; batches it cannot run fail with
  * FINCH_ERR_UNSUPPORTED.  AUTO (default) takes OWNER when the batch has enough
- * problems to fill the chip's compute units in whole rounds, else SEPARATE.
- * One context must not run on two streams at the same time. */
+ * problems to fill the chip's compute units in whole rounds, else SEPARATE. */
 typedef enum {
   FINCH_OPT_STEP_PATH = 1,
   /* tuning: target number of keys one workgroup of the two-pass bf16 scoring

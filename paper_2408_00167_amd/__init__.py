@@ -31,7 +31,7 @@ EXPORTED_SYMBOLS = (
     "finch_compact", "finch_step", "finch_schedule", "finch_schedule_mode", "finch_last_hip_error",
     "finch_status_string", "finch_version", "finch_profile", "finch_profile_read",
     "finch_set_option", "finch_set_reposition", "finch_prompt_lse", "finch_loop", "finch_loop_workspace_size",
-    "finch_step_static", "finch_static_scratch_bytes",
+    "finch_step_static", "finch_static_scratch_bytes", "finch_loop_check",
 )
 
 KERNEL_NAMES = ("rowstats", "lse", "colsum", "select", "gather", "owner", "prompt_lse")
@@ -121,6 +121,8 @@ def load_library() -> ctypes.CDLL:
     lib.finch_step_static.restype = ctypes.c_int
     lib.finch_static_scratch_bytes.argtypes = []
     lib.finch_static_scratch_bytes.restype = sz
+    lib.finch_loop_check.argtypes = [P(finch_config), P(finch_problem), P(i32), i32]
+    lib.finch_loop_check.restype = ctypes.c_int
     lib.finch_set_option.argtypes = [vp, i32, i64]
     lib.finch_set_option.restype = ctypes.c_int
     lib.finch_version.argtypes = []
@@ -246,6 +248,13 @@ def finch_loop(ctx, host_desc, dev_desc: int, host_step_first, dev_step_first: i
            "finch_loop", ctx)
 
 
+def finch_loop_check(dtype: int, head_dim: int, group_size: int, host_desc, host_step_first,
+                     n_steps: int) -> int:
+    """Host-only argument checks of finch_loop; returns the status (no exception)."""
+    cfg = finch_config(dtype, head_dim, group_size, 0)
+    return int(load_library().finch_loop_check(ctypes.byref(cfg), host_desc, host_step_first, n_steps))
+
+
 def finch_version() -> int:
     return load_library().finch_version()
 
@@ -338,9 +347,18 @@ class Finch:
     def reserve(self, batch: Batch) -> int:
         import torch
         need = finch_workspace_size(self.ctx, batch.host, batch.n)
-        if self.ws is None or self.ws.numel() < need:
-            self.ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
+        self._grow(need)
         return need
+
+    def _grow(self, need: int) -> None:
+        """A larger workspace replaces the present one only once nothing enqueued on any
+        stream can still be using it (growth is rare; pre-size with reserve outside hot
+        loops)."""
+        import torch
+        if self.ws is None or self.ws.numel() < need:
+            if self.ws is not None:
+                torch.cuda.synchronize(self.device)
+            self.ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
 
     def _run(self, name: str, batch: Batch, stream=None):
         import torch
@@ -375,8 +393,7 @@ class Finch:
     def reserve_loop(self, lb: LoopBatch) -> int:
         import torch
         need = finch_loop_workspace_size(self.ctx, lb.batch.host, lb.host_first, lb.n_steps)
-        if self.ws is None or self.ws.numel() < need:
-            self.ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
+        self._grow(need)
         return need
 
     def loop(self, lb: LoopBatch, stream=None):

@@ -4,9 +4,11 @@
 #include <cmath>
 #include <cstdint>
 #include <cstdio>
+#include <algorithm>
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <vector>
 
 #include "finch_internal.h"
 
@@ -27,6 +29,10 @@ struct finch_ctx {
   finch_reposition repos;  // {OFF, ASCENDING}: plain copies
   int layer_group;         // > 1: runs of that many problems share one selection
   void* static_scratch;    // this device's copy of the file-scope scratch array (finch_step_static)
+  // finch_loop: fingerprint of the last descriptor set whose slots were found free of
+  // overlaps (the check is repeated only when the descriptors change)
+  uint64_t loop_checked_hash;
+  bool loop_checked;
 };
 
 // Scratch of finch_step_static: the workspace of a step, held by the library itself so
@@ -396,6 +402,102 @@ finch_status check_steps(const int32_t* first, int32_t n_steps, int32_t* n_desc,
   return FINCH_OK;
 }
 
+// ---- finch_loop: slots must not touch each other's memory
+struct Span {
+  uintptr_t lo, hi;  // [lo, hi)
+  int32_t slot;
+};
+
+void add_span(std::vector<Span>& v, const void* p, size_t bytes, int32_t slot) {
+  if (!p || bytes == 0) return;
+  const uintptr_t a = reinterpret_cast<uintptr_t>(p);
+  v.push_back(Span{a, a + bytes, slot});
+}
+
+// Sorts by start and merges spans of one slot that touch or overlap (the ping-pong
+// slabs of a chunk loop repeat every other step).
+void merge_own(std::vector<Span>& v) {
+  std::sort(v.begin(), v.end(), [](const Span& a, const Span& b) { return a.lo < b.lo; });
+  size_t out = 0;
+  for (size_t i = 0; i < v.size(); ++i) {
+    if (out > 0 && v[i].lo <= v[out - 1].hi) {
+      if (v[i].hi > v[out - 1].hi) v[out - 1].hi = v[i].hi;
+    } else {
+      v[out++] = v[i];
+    }
+  }
+  v.resize(out);
+}
+
+uint64_t fingerprint(const void* data, size_t bytes, uint64_t seed) {
+  const unsigned char* p = static_cast<const unsigned char*>(data);
+  uint64_t h[4] = {seed ^ 0x9e3779b97f4a7c15ull, seed + 0xbf58476d1ce4e5b9ull, seed ^ 0x94d049bb133111ebull,
+                   seed + 0x2545f4914f6cdd1dull};
+  size_t i = 0;
+  for (; i + 32 <= bytes; i += 32) {
+    uint64_t w[4];
+    std::memcpy(w, p + i, 32);
+    for (int k = 0; k < 4; ++k) h[k] = (h[k] ^ w[k]) * 0xff51afd7ed558ccdull + (h[k] >> 29);
+  }
+  uint64_t tail = 0;
+  if (i < bytes) std::memcpy(&tail, p + i, bytes - i < 8 ? bytes - i : 8);
+  uint64_t r = tail ^ (static_cast<uint64_t>(bytes) << 1);
+  for (int k = 0; k < 4; ++k) r = (r ^ h[k]) * 0xc4ceb9fe1a85ec53ull + (r >> 31);
+  return r;
+}
+
+// The rule of finch_loop: a slot runs through its steps without regard to the other
+// slots, so nothing a slot writes (k_out, v_out, scores, idx of any of its steps) may
+// overlap what another slot writes or reads (q, q_doc, k_*, v_*, lse_extra, scores).
+finch_status check_slot_overlaps(const finch_ctx* ctx, const finch_problem* hd, const int32_t* first,
+                                 int32_t n_steps, int32_t n_slots) {
+  if (n_slots <= 1) return FINCH_OK;
+  const size_t rb = static_cast<size_t>(ctx->row_bytes);
+  const int G = ctx->cfg.group_size;
+  std::vector<Span> writes, reads, own_w, own_r;
+  for (int32_t slot = 0; slot < n_slots; ++slot) {
+    own_w.clear();
+    own_r.clear();
+    for (int32_t s = 0; s < n_steps; ++s) {
+      if (slot >= first[s + 1] - first[s]) break;
+      const finch_problem& pb = hd[first[s] + slot];
+      const size_t N = static_cast<size_t>(pb.c) + static_cast<size_t>(pb.m);
+      const size_t rr = static_cast<size_t>(pb.r) < N ? static_cast<size_t>(pb.r) : N;
+      add_span(own_w, pb.k_out, rr * rb, slot);
+      add_span(own_w, pb.v_out, rr * rb, slot);
+      add_span(own_w, pb.scores, N * sizeof(float), slot);
+      add_span(own_w, pb.idx, rr * sizeof(int32_t), slot);
+      add_span(own_r, pb.q, static_cast<size_t>(G) * pb.n_que * rb, slot);
+      add_span(own_r, pb.q_doc, static_cast<size_t>(G) * pb.m * rb, slot);
+      add_span(own_r, pb.k_cache, static_cast<size_t>(pb.c) * rb, slot);
+      add_span(own_r, pb.v_cache, static_cast<size_t>(pb.c) * rb, slot);
+      add_span(own_r, pb.k_chunk, static_cast<size_t>(pb.m) * rb, slot);
+      add_span(own_r, pb.v_chunk, static_cast<size_t>(pb.m) * rb, slot);
+      add_span(own_r, pb.lse_extra, static_cast<size_t>(G) * pb.n_que * sizeof(float), slot);
+    }
+    merge_own(own_w);
+    merge_own(own_r);
+    writes.insert(writes.end(), own_w.begin(), own_w.end());
+    reads.insert(reads.end(), own_r.begin(), own_r.end());
+  }
+  std::sort(writes.begin(), writes.end(), [](const Span& a, const Span& b) { return a.lo < b.lo; });
+  // spans of one slot are disjoint now, so two neighbours that overlap belong to two slots;
+  // `reach` carries the furthest end seen so far and the slot it belongs to
+  uintptr_t reach = 0;
+  for (size_t i = 0; i < writes.size(); ++i) {
+    if (i > 0 && writes[i].lo < reach) return FINCH_ERR_INVALID_ARG;
+    if (writes[i].hi > reach) reach = writes[i].hi;
+  }
+  // the write spans are disjoint and sorted: look each read span up
+  for (const Span& r : reads) {
+    auto it = std::upper_bound(writes.begin(), writes.end(), r.lo,
+                               [](uintptr_t x, const Span& w) { return x < w.hi; });  // first span ending after r.lo
+    for (; it != writes.end() && it->lo < r.hi; ++it)
+      if (it->slot != r.slot) return FINCH_ERR_INVALID_ARG;
+  }
+  return FINCH_OK;
+}
+
 // One step with its launches sized by `pl` (finch_step and finch_step_static).
 finch_status step_planned(finch_ctx* ctx, const finch_problem* host_desc, const finch_problem* dev_desc,
                           int32_t n, const Plan& pl, void* ws, size_t ws_bytes, void* stream) {
@@ -444,6 +546,8 @@ finch_status finch_create(const finch_config* cfg, finch_ctx** out) {
   ctx->repos.order = FINCH_ORDER_ASCENDING;
   ctx->repos.base = 10000.0;
   ctx->static_scratch = nullptr;
+  ctx->loop_checked = false;
+  ctx->loop_checked_hash = 0;
   hipError_t e = hipGetDevice(&ctx->device);
   if (e == hipSuccess) e = static_scratch_address(ctx->device, &ctx->static_scratch);
   if (e == hipSuccess) {
@@ -693,6 +797,16 @@ finch_status finch_loop(finch_ctx* ctx, const finch_problem* host_desc, const fi
   Plan pl;
   if ((st = make_plan(ctx, host_desc, n_desc, pl, n_slots)) != FINCH_OK) return st;
   if ((st = validate(ctx, host_desc, n_desc, kNeedQK | kNeedIdx | kNeedGather)) != FINCH_OK) return st;
+  {
+    // overlaps between slots: checked once per descriptor set
+    uint64_t h = fingerprint(host_desc, static_cast<size_t>(n_desc) * sizeof(finch_problem), 1);
+    h = fingerprint(host_step_first, static_cast<size_t>(n_steps + 1) * sizeof(int32_t), h);
+    if (!ctx->loop_checked || ctx->loop_checked_hash != h) {
+      if ((st = check_slot_overlaps(ctx, host_desc, host_step_first, n_steps, n_slots)) != FINCH_OK) return st;
+      ctx->loop_checked = true;
+      ctx->loop_checked_hash = h;
+    }
+  }
   if ((st = check_workspace(pl, ws, ws_bytes)) != FINCH_OK) return st;
   if (n_desc == 0 || pl.tiles_max == 0) return FINCH_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -717,6 +831,31 @@ finch_status finch_loop(finch_ctx* ctx, const finch_problem* host_desc, const fi
       return st;
   }
   return FINCH_OK;
+}
+
+finch_status finch_loop_check(const finch_config* cfg, const finch_problem* host_desc,
+                              const int32_t* host_step_first, int32_t n_steps) {
+  if (!cfg) return FINCH_ERR_INVALID_ARG;
+  if (cfg->dtype != FINCH_F32 && cfg->dtype != FINCH_BF16) return FINCH_ERR_UNSUPPORTED;
+  if (cfg->head_dim != 64 && cfg->head_dim != 128) return FINCH_ERR_UNSUPPORTED;
+  if (cfg->group_size < 1 || cfg->group_size > 64) return FINCH_ERR_UNSUPPORTED;
+  int32_t n_desc, n_slots;
+  finch_status st = check_steps(host_step_first, n_steps, &n_desc, &n_slots);
+  if (st != FINCH_OK) return st;
+  if (n_desc > 0 && !host_desc) return FINCH_ERR_INVALID_ARG;
+  // a context on the stack that only carries the settings the checks read (no GPU is touched)
+  finch_ctx tmp;
+  std::memset(&tmp, 0, sizeof(tmp));
+  tmp.cfg = *cfg;
+  tmp.row_bytes = cfg->head_dim * (cfg->dtype == FINCH_BF16 ? 2 : 4);
+  tmp.layer_group = 1;
+  for (int32_t i = 0; i < n_desc; ++i) {
+    const finch_problem& pb = host_desc[i];
+    if (pb.n_que < 0 || pb.c < 0 || pb.m < 0 || pb.r < 0) return FINCH_ERR_INVALID_ARG;
+    if (static_cast<int64_t>(pb.c) + pb.m > (1 << 24)) return FINCH_ERR_CAPACITY;
+  }
+  if ((st = validate(&tmp, host_desc, n_desc, kNeedQK | kNeedIdx | kNeedGather)) != FINCH_OK) return st;
+  return check_slot_overlaps(&tmp, host_desc, host_step_first, n_steps, n_slots);
 }
 
 finch_status finch_schedule(int64_t n_cont, int32_t m, int64_t k, int32_t* r_out, int32_t r_len) {

@@ -117,9 +117,10 @@ __global__ __launch_bounds__(kThreads, 4) void rowstats_bf16(LaunchParams prm) {
             const float mu = (m_run[q] == -kInf) ? 0.f : m_run[q];
 #pragma unroll
             for (int v = 0; v < 16; ++v) z += fast_exp2(__builtin_fmaf(a[v], sc, -mu));
-            // (a lane that has no reference yet because every key it has seen was masked takes
-            // one as soon as it sees a key: its sums so far are empty)
-            move = __any(!(z <= 0x1p64f) || (m_run[q] == -kInf && z > 0.f));
+            // (A lane without a reference - every key it has seen was masked - never meets a
+            // key it sees later on: masked keys are the ones past a limit, a wave's blocks come
+            // in ascending key order, and inside a block a lane's keys ascend too.)
+            move = __any(!(z <= 0x1p64f));
           }
           if (move) {
             float bm = fmaxf(a[0], a[1]);

@@ -74,3 +74,68 @@ def test_no_gpu_means_loud_failure_not_fallback():
     with pytest.raises(F.FinchError) as e:
         F.finch_create(F.FINCH_BF16, 128, 4)
     assert e.value.status == F.FINCH_ERR_HIP
+
+
+def _loop_descs(n_slots, n_steps, d=128, c_step=8, m=64, overlap=None):
+    """Descriptors of a chunk loop laid out by hand in a made-up address space (the
+    library only compares the pointers): per slot a document K and V, two ping-pong
+    cache slabs, idx and scores per step.  `overlap` plants one violation."""
+    rb = d * 2
+    cap = c_step * n_steps
+    slot_bytes = 2 * (m * n_steps) * rb + 4 * cap * rb + n_steps * (cap * 4 + (cap + m) * 4) + 4096
+    slot_bytes = (slot_bytes + 255) // 256 * 256
+    base0 = 1 << 32
+    hd = (F.finch_problem * (n_slots * n_steps))()
+    first = (ctypes.c_int32 * (n_steps + 1))(*[s * n_slots for s in range(n_steps + 1)])
+    qaddr = base0 - (1 << 20)
+    for s in range(n_steps):
+        for j in range(n_slots):
+            b = base0 + j * slot_bytes
+            kdoc, vdoc = b, b + m * n_steps * rb
+            slabs = vdoc + m * n_steps * rb
+            kslab = [slabs, slabs + cap * rb]
+            vslab = [slabs + 2 * cap * rb, slabs + 3 * cap * rb]
+            misc = slabs + 4 * cap * rb
+            pd = hd[s * n_slots + j]
+            pd.q = qaddr                      # one prompt block read by every slot
+            pd.n_que, pd.c, pd.m, pd.r = 4, c_step * s, m, c_step * (s + 1)
+            pd.k_cache, pd.v_cache = (kslab[s % 2], vslab[s % 2]) if s else (None, None)
+            pd.k_chunk, pd.v_chunk = kdoc + s * m * rb, vdoc + s * m * rb
+            pd.k_out, pd.v_out = kslab[(s + 1) % 2], vslab[(s + 1) % 2]
+            pd.idx = misc + s * (cap * 4 + (cap + m) * 4)
+            pd.scores = pd.idx + cap * 4
+    if overlap == "write_into_other_slots_chunk":
+        hd[1 * n_slots + 0].k_out = hd[2 * n_slots + 1].k_chunk      # slot 0 writes keys slot 1 reads later
+    elif overlap == "shared_idx":
+        hd[0 * n_slots + 2].idx = hd[1 * n_slots + 3].idx            # two slots write one index array
+    elif overlap == "partial":
+        hd[2 * n_slots + 1].v_out = hd[2 * n_slots + 2].v_cache + rb * 3
+    return hd, first
+
+
+def test_loop_check_accepts_disjoint_slots_and_rejects_overlaps_between_slots():
+    n_slots, n_steps = 5, 4
+    hd, first = _loop_descs(n_slots, n_steps)
+    assert F.finch_loop_check(F.FINCH_BF16, 128, 1, hd, first, n_steps) == F.FINCH_OK
+    for bad in ("write_into_other_slots_chunk", "shared_idx", "partial"):
+        hd, first = _loop_descs(n_slots, n_steps, overlap=bad)
+        assert F.finch_loop_check(F.FINCH_BF16, 128, 1, hd, first, n_steps) == F.FINCH_ERR_INVALID_ARG, bad
+    # a slot may read what it wrote itself in an earlier step (that is the chunk loop),
+    # and one slot alone has nobody to collide with
+    hd, first = _loop_descs(1, n_steps)
+    assert F.finch_loop_check(F.FINCH_BF16, 128, 1, hd, first, n_steps) == F.FINCH_OK
+    # the other checks of finch_loop are made too: a step table that grows, an output on its source
+    hd, first = _loop_descs(n_slots, n_steps)
+    grow = (ctypes.c_int32 * (n_steps + 1))(0, 2, 7, 12, 20)
+    assert F.finch_loop_check(F.FINCH_BF16, 128, 1, hd, grow, n_steps) == F.FINCH_ERR_INVALID_ARG
+    hd[n_slots].k_out = hd[n_slots].k_chunk
+    assert F.finch_loop_check(F.FINCH_BF16, 128, 1, hd, first, n_steps) == F.FINCH_ERR_INVALID_ARG
+    assert F.finch_loop_check(F.FINCH_BF16, 96, 1, hd, first, n_steps) == F.FINCH_ERR_UNSUPPORTED
+
+
+def test_loop_check_many_slots_is_fast():
+    import time
+    hd, first = _loop_descs(1024, 8)
+    t0 = time.perf_counter()
+    assert F.finch_loop_check(F.FINCH_BF16, 128, 1, hd, first, 8) == F.FINCH_OK
+    assert time.perf_counter() - t0 < 0.5

@@ -78,26 +78,26 @@ def run_full(name, n_sample, seed, path=F.FINCH_PATH_AUTO):
 
 @pytest.mark.timeout(600)
 def test_c2_full_size():
-    run_full("C2", 6, seed=2)
+    run_full("C2", 12, seed=2)
 
 
 @pytest.mark.timeout(600)
 def test_c3_full_size():
-    run_full("C3", 4, seed=3)
+    run_full("C3", 8, seed=3)
 
 
 @pytest.mark.timeout(900)
 def test_c4_full_size():
-    run_full("C4", 4, seed=4)
+    run_full("C4", 16, seed=4)
 
 
 @pytest.mark.timeout(900)
 def test_c4_full_size_one_kernel_per_stage():
     """AUTO runs these batches with one workgroup per problem; the per-stage kernels
     are checked at full size too."""
-    run_full("C4", 2, seed=14, path=F.FINCH_PATH_SEPARATE)
+    run_full("C4", 6, seed=14, path=F.FINCH_PATH_SEPARATE)
 
 
 @pytest.mark.timeout(1200)
 def test_c5_full_size():
-    run_full("C5", 3, seed=5)
+    run_full("C5", 8, seed=5)

@@ -160,6 +160,21 @@ def test_many_slices_use_the_merge_kernel():
     fin.close()
 
 
+# A weight below 2^-126 cannot be held in fp32 (the kernels flush it to zero), so a score
+# is only held to the stated tolerance while such weights cannot matter to it: above
+# 1e-30 the flushed weights of all rows together stay below 1e-5 of the score.
+FP32_UNDERFLOW_BOUND = 1e-30
+
+
+def _check_above_underflow(got, want, what):
+    """the stated per-element tolerance on every key whose score fp32 can hold; the others
+    must be tiny too"""
+    big = want > FP32_UNDERFLOW_BOUND
+    rel = np.abs(got[big] - want[big]) / want[big]
+    assert rel.max() <= H.SCORE_TOL["bf16"], f"{what}: rel err {rel.max():.3e} at key {np.nonzero(big)[0][rel.argmax()]}"
+    assert (got[~big] <= 2 * FP32_UNDERFLOW_BOUND).all(), what
+
+
 def test_large_logits_do_not_overflow():
     """Logits of several hundred: the running maximum keeps exp2 in range."""
     say("large_logits")
@@ -172,8 +187,7 @@ def test_large_logits_do_not_overflow():
     want = O.key_scores(W.to_numpy_storage(ts[0]["q"]), W.to_numpy_storage(ts[0]["k_cache"]),
                         W.to_numpy_storage(ts[0]["k_chunk"]))
     assert np.isfinite(got).all() and abs(got.sum() - 8.0) < 1e-3
-    big = want > 1e-6                       # tiny tails may underflow differently
-    assert np.abs(got[big] - want[big]).max() / want[big].max() < 2e-3
+    _check_above_underflow(got, want, "large logits")
     fin.close()
 
 
@@ -197,8 +211,7 @@ def test_logits_far_from_the_first_blocks_reference(kramp, path):
         want = O.key_scores(W.to_numpy_storage(t["q"]), W.to_numpy_storage(t["k_cache"]),
                             W.to_numpy_storage(t["k_chunk"]))
         assert np.isfinite(got).all() and abs(got.sum() - R) < 1e-3 * R
-        big = want > 1e-6
-        assert np.abs(got[big] - want[big]).max() / want[big].max() < 2e-3
+        _check_above_underflow(got, want, f"logit ramp x{kramp:.3g} {path}")
     fin.close()
 
 
