@@ -45,7 +45,8 @@ typedef enum {
   FINCH_ERR_UNSUPPORTED = -2, /* dtype / head_dim / group size not built          */
   FINCH_ERR_CAPACITY = -3,    /* a size exceeds what one launch can index         */
   FINCH_ERR_WORKSPACE = -4,   /* workspace missing, misaligned or too small       */
-  FINCH_ERR_HIP = -5          /* a HIP call failed; see finch_last_hip_error      */
+  FINCH_ERR_HIP = -5,         /* a HIP call failed; see finch_last_hip_error      */
+  FINCH_ERR_TIMEOUT = -6      /* finch_workspace_status: workgroups waited in vain */
 } finch_status;
 
 typedef enum { FINCH_F32 = 0, FINCH_BF16 = 1 } finch_dtype;
@@ -159,8 +160,9 @@ finch_status finch_compact(finch_ctx* ctx, const finch_problem* host_desc,
  * and at most 32768 kept rows per problem, else FINCH_ERR_CAPACITY).  Rotation is
  * computed in fp32 (angles reduced in fp64); bf16 results are rounded to nearest
  * even; a shift of 0 leaves the key bit-identical.  NULL, or {OFF, ASCENDING},
- * restores the plain copy.  With FINCH_ORDER_RANK batches run with one kernel per
- * stage (FINCH_PATH_OWNER is refused with FINCH_ERR_UNSUPPORTED). */
+ * restores the plain copy.  With FINCH_ORDER_RANK the one-workgroup-per-problem kernels
+ * take batches that keep at most 2048 rows per problem (the workgroup ranks its kept rows
+ * in LDS); others run with one kernel per stage (FINCH_PATH_OWNER: FINCH_ERR_UNSUPPORTED). */
 typedef enum { FINCH_ROPE_OFF = 0, FINCH_ROPE_HALF = 1, FINCH_ROPE_INTERLEAVED = 2 } finch_rope_pairing;
 typedef enum { FINCH_ORDER_ASCENDING = 0, FINCH_ORDER_RANK = 1 } finch_order;
 typedef struct {
@@ -215,6 +217,17 @@ finch_status finch_loop(finch_ctx* ctx, const finch_problem* host_desc,
                         const int32_t* dev_step_first, int32_t n_steps, void* workspace,
                         size_t workspace_bytes, void* stream);
 
+/* The first word of a workspace is the status word of the launches that used it last.
+ * Only one thing sets it: with FINCH_OPT_LAYER_GROUP > 1 the workgroups of a layer wait
+ * for each other inside the one-workgroup-per-problem kernels, at most about 0.2 s each
+ * time; a workgroup whose wait runs out sets the word and goes on with the scores it
+ * finds, so the launch always ends, but its selection is then not the layer's.  This
+ * call waits for `stream`, copies the word to *flags and returns FINCH_ERR_TIMEOUT if it
+ * is not zero (which takes a chip on which other work keeps some of the batch's
+ * workgroups from starting).  While FINCH_OPT_LAYER_GROUP > 1 every finch_step and
+ * finch_loop call clears the word first; with the option at 1 the call reports 0. */
+finch_status finch_workspace_status(finch_ctx* ctx, const void* workspace, void* stream, int32_t* flags);
+
 /* Host-only: the argument checks of finch_loop on a descriptor set, without a context
  * and without touching a GPU (the pointers are only compared, never followed): step
  * table, pointers and alignment, outputs that overlap their own sources, and the rule
@@ -257,8 +270,11 @@ typedef enum {
    * run's score vectors head by head, select once on the sum and write the same
    * indices to every problem of the run; each head compacts its own rows.  The
    * per-problem scores stay as they are.  1 (default): one selection per problem.
-   * Runs are processed with one kernel per stage; FINCH_ORDER_RANK is refused
-   * (FINCH_ERR_UNSUPPORTED) while L > 1. */
+   * FINCH_ORDER_RANK is refused (FINCH_ERR_UNSUPPORTED) while L > 1.  The
+   * one-workgroup-per-problem kernels take such batches when L <= 16 and the batch has
+   * no more problems than the chip has compute units: the L workgroups of a run then
+   * wait for each other's scores inside the launch (see finch_workspace_status);
+   * other batches run with one kernel per stage. */
   FINCH_OPT_LAYER_GROUP = 4
 } finch_option;
 typedef enum { FINCH_PATH_AUTO = 0, FINCH_PATH_SEPARATE = 1, FINCH_PATH_OWNER = 3 } finch_path;

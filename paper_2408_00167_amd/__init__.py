@@ -22,6 +22,7 @@ FINCH_ERR_UNSUPPORTED = -2
 FINCH_ERR_CAPACITY = -3
 FINCH_ERR_WORKSPACE = -4
 FINCH_ERR_HIP = -5
+FINCH_ERR_TIMEOUT = -6
 
 FINCH_F32 = 0
 FINCH_BF16 = 1
@@ -32,6 +33,7 @@ EXPORTED_SYMBOLS = (
     "finch_status_string", "finch_version", "finch_profile", "finch_profile_read",
     "finch_set_option", "finch_set_reposition", "finch_prompt_lse", "finch_loop", "finch_loop_workspace_size",
     "finch_step_static", "finch_static_scratch_bytes", "finch_loop_check",
+    "finch_workspace_status",
 )
 
 KERNEL_NAMES = ("rowstats", "lse", "colsum", "select", "gather", "owner", "prompt_lse")
@@ -121,6 +123,8 @@ def load_library() -> ctypes.CDLL:
     lib.finch_step_static.restype = ctypes.c_int
     lib.finch_static_scratch_bytes.argtypes = []
     lib.finch_static_scratch_bytes.restype = sz
+    lib.finch_workspace_status.argtypes = [vp, vp, vp, P(i32)]
+    lib.finch_workspace_status.restype = ctypes.c_int
     lib.finch_loop_check.argtypes = [P(finch_config), P(finch_problem), P(i32), i32]
     lib.finch_loop_check.restype = ctypes.c_int
     lib.finch_set_option.argtypes = [vp, i32, i64]
@@ -384,6 +388,18 @@ class Finch:
         import torch
         s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
         finch_step_static(self.ctx, batch.host, batch.dev_ptr, batch.n, s)
+
+    def workspace_status(self, stream=None) -> int:
+        """Waits for the stream; 0, or the status word of the last launches (FINCH_ERR_TIMEOUT raised)."""
+        import torch
+        s = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
+        flags = ctypes.c_int32(0)
+        if self.ws is None:
+            return 0
+        _check(load_library().finch_workspace_status(self.ctx, ctypes.c_void_p(self.ws.data_ptr()),
+                                                     ctypes.c_void_p(s), ctypes.byref(flags)),
+               "finch_workspace_status", self.ctx)
+        return int(flags.value)
 
     def prompt_lse(self, batch: Batch, stream=None):
         import torch

@@ -60,7 +60,8 @@ struct Plan {
   int32_t own_row_chunk = 32;
   size_t own_lds = 0;
   size_t lds_bytes = 0;
-  size_t off_stats = 0, off_lse = 0, off_scores = 0, off_layer = 0, total = 0;
+  size_t off_stats = 0, off_lse = 0, off_scores = 0, off_layer = 0, off_sync = 0, total = 0;
+  int32_t sync_words = 0;  // counters of the layer runs (workspace word 0 is the status word)
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -137,7 +138,7 @@ finch_status make_plan(const finch_ctx* ctx, const finch_problem* hd, int32_t n_
     pl.own_lds = finch::owner_lds_bytes(ctx->cfg.head_dim, orc);
     pl.own_ok = pl.own_lds <= ctx->max_lds;
   }
-  size_t off = 0;
+  size_t off = 256;  // the first word of the workspace is the status word of the launches (finch_workspace_status)
   pl.off_stats = off;
   const size_t na = static_cast<size_t>(n_alloc);
   off = align_up(off + na * pl.tiles_max * pl.rpad_max * sizeof(float2), 256);
@@ -148,6 +149,11 @@ finch_status make_plan(const finch_ctx* ctx, const finch_problem* hd, int32_t n_
   pl.off_layer = off;
   if (ctx->layer_group > 1)
     off = align_up(off + (na / ctx->layer_group + 1) * pl.score_stride * sizeof(float), 256);
+  pl.off_sync = off;
+  if (ctx->layer_group > 1) {
+    pl.sync_words = static_cast<int32_t>(2 * (na / ctx->layer_group + 1));
+    off = align_up(off + static_cast<size_t>(pl.sync_words) * sizeof(int32_t), 256);
+  }
   pl.total = off;
   return FINCH_OK;
 }
@@ -207,7 +213,7 @@ finch_status check_common(const finch_ctx* ctx, const finch_problem* hd, const f
 }
 
 finch_status check_workspace(const Plan& pl, const void* ws, size_t ws_bytes) {
-  if (pl.total == 0) return FINCH_OK;
+  if (pl.total <= 256) return FINCH_OK;
   if (!ws || !aligned(ws, 256) || ws_bytes < pl.total) return FINCH_ERR_WORKSPACE;
   return FINCH_OK;
 }
@@ -233,7 +239,12 @@ LaunchParams make_params(const finch_ctx* ctx, const finch_problem* dd, int32_t 
   p.ws_scores = reinterpret_cast<float*>(base + pl.off_scores);
   p.lds_bytes = static_cast<uint32_t>(pl.lds_bytes);
   p.rope_pairing = ctx->repos.pairing;
+  p.rank_order = ctx->repos.order == FINCH_ORDER_RANK ? 1 : 0;
   p.rope_log2_base = std::log2(ctx->repos.base);
+  p.layer_group = ctx->layer_group;
+  p.layer_sync = base ? reinterpret_cast<int32_t*>(base + pl.off_sync) : nullptr;
+  p.layer_err = reinterpret_cast<int32_t*>(base);
+  p.spin_ticks = 20 * 1000 * 1000;  // 0.2 s
   return p;
 }
 
@@ -292,9 +303,20 @@ bool repositioning(const finch_ctx* ctx) {
 }
 
 bool owner_wanted(const finch_ctx* ctx, const Plan& pl, int32_t n) {
-  // a workgroup that owns one problem re-positions only to ascending slots and cannot
-  // share a selection with other problems
-  if (!pl.own_ok || n <= 0 || ctx->repos.order != FINCH_ORDER_ASCENDING || ctx->layer_group > 1)
+  if (!pl.own_ok || n <= 0) return false;
+  // slots by score rank: the workgroup sorts its kept rows in LDS (their indices and one
+  // 64-bit record each, padded to a power of two, behind the selection scratch), and a
+  // layer's heads would have to share the slots
+  if (ctx->repos.order == FINCH_ORDER_RANK) {
+    size_t npad = 2;
+    while (npad < static_cast<size_t>(pl.r_max)) npad <<= 1;
+    if (static_cast<size_t>(pl.r_max) * 4 + 8 + npad * 8 > finch::kOwnerSelectBytes || ctx->layer_group > 1)
+      return false;
+  }
+  // the workgroups of a layer wait for each other: all of them must be on the chip at once
+  // (one workgroup per compute unit), and a run's score vectors are added up by every one of them
+  if (ctx->layer_group > 1 &&
+      (ctx->layer_group > finch::kOwnerMaxLayer || n > (ctx->n_cu > 0 ? ctx->n_cu : 256)))
     return false;
   if (ctx->step_path == FINCH_PATH_OWNER) return true;
   if (pl.has_doc) return ctx->step_path == FINCH_PATH_AUTO;  // the only kernels with those rows
@@ -308,6 +330,9 @@ finch_status run_owner(finch_ctx* ctx, LaunchParams p, const Plan& pl, int stage
   p.row_chunk = pl.own_row_chunk;
   p.lds_bytes = static_cast<uint32_t>(pl.own_lds);
   hipError_t e;
+  if (stages && ctx->layer_group > 1) {
+    if ((e = finch::launch_zero_words(p.layer_sync, pl.sync_words, p.layer_err, s)) != hipSuccess) return hip_fail(ctx, e);
+  }
   {
     ProfScope ps(ctx, FINCH_KERNEL_OWNER, s);
     e = pl.has_doc ? finch::launch_owner_doc_bf16(ctx->cfg.head_dim, p, stages, s)
@@ -508,6 +533,10 @@ finch_status step_planned(finch_ctx* ctx, const finch_problem* host_desc, const 
   if (n == 0) return FINCH_OK;
   const LaunchParams p = make_params(ctx, dev_desc, n, pl, ws);
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (ctx->layer_group > 1) {  // the status word starts every such call at zero, whatever path it takes
+    const hipError_t e = finch::launch_zero_words(nullptr, 0, p.layer_err, s);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+  }
   if (pl.tiles_max > 0 && owner_wanted(ctx, pl, n)) return run_owner(ctx, p, pl, /*stages=*/1, s);
   if ((ctx->step_path == FINCH_PATH_OWNER || pl.has_doc) && pl.tiles_max > 0) return FINCH_ERR_UNSUPPORTED;
   if ((st = run_score(ctx, p, pl, s)) != FINCH_OK) return st;
@@ -797,6 +826,10 @@ finch_status finch_loop(finch_ctx* ctx, const finch_problem* host_desc, const fi
   Plan pl;
   if ((st = make_plan(ctx, host_desc, n_desc, pl, n_slots)) != FINCH_OK) return st;
   if ((st = validate(ctx, host_desc, n_desc, kNeedQK | kNeedIdx | kNeedGather)) != FINCH_OK) return st;
+  for (int32_t i = 0; i < n_steps && ctx->layer_group > 1; ++i) {
+    const int32_t f = host_step_first[i];
+    if ((st = check_layer_runs(ctx, host_desc + f, host_step_first[i + 1] - f)) != FINCH_OK) return st;
+  }
   {
     // overlaps between slots: checked once per descriptor set
     uint64_t h = fingerprint(host_desc, static_cast<size_t>(n_desc) * sizeof(finch_problem), 1);
@@ -810,11 +843,18 @@ finch_status finch_loop(finch_ctx* ctx, const finch_problem* host_desc, const fi
   if ((st = check_workspace(pl, ws, ws_bytes)) != FINCH_OK) return st;
   if (n_desc == 0 || pl.tiles_max == 0) return FINCH_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (ctx->layer_group > 1) {
+    const hipError_t e = finch::launch_zero_words(nullptr, 0, static_cast<int32_t*>(ws), s);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+  }
   if (owner_wanted(ctx, pl, n_slots)) {
     LaunchParams p = make_params(ctx, dev_desc, n_desc, pl, ws);
     p.row_chunk = pl.own_row_chunk;
     p.lds_bytes = static_cast<uint32_t>(pl.own_lds);
     hipError_t e;
+    if (ctx->layer_group > 1) {
+      if ((e = finch::launch_zero_words(p.layer_sync, pl.sync_words, p.layer_err, s)) != hipSuccess) return hip_fail(ctx, e);
+    }
     {
       ProfScope ps(ctx, FINCH_KERNEL_OWNER, s);
       e = pl.has_doc
@@ -831,6 +871,17 @@ finch_status finch_loop(finch_ctx* ctx, const finch_problem* host_desc, const fi
       return st;
   }
   return FINCH_OK;
+}
+
+finch_status finch_workspace_status(finch_ctx* ctx, const void* workspace, void* stream, int32_t* flags) {
+  if (!ctx || !workspace || !flags) return FINCH_ERR_INVALID_ARG;
+  *flags = 0;
+  if (ctx->layer_group <= 1) return FINCH_OK;  // nothing sets the word then (and nothing has cleared it)
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = hipMemcpyAsync(flags, workspace, sizeof(int32_t), hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  return *flags == 0 ? FINCH_OK : FINCH_ERR_TIMEOUT;
 }
 
 finch_status finch_loop_check(const finch_config* cfg, const finch_problem* host_desc,
@@ -896,6 +947,7 @@ const char* finch_status_string(finch_status s) {
     case FINCH_ERR_CAPACITY: return "size exceeds capacity";
     case FINCH_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case FINCH_ERR_HIP: return "HIP call failed";
+    case FINCH_ERR_TIMEOUT: return "workgroups of a layer waited for each other in vain";
   }
   return "unknown status";
 }

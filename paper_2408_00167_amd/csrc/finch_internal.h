@@ -22,6 +22,10 @@ __host__ __device__ inline int stream_slices(int n_keys, int slice_keys) {
 }
 // One-workgroup-per-problem path: most prompt rows staged per pass over the keys.
 constexpr int kOwnerMaxRowChunk = 256;
+// LDS the one-workgroup-per-problem kernels keep behind their selection scratch (kept indices etc.).
+constexpr size_t kOwnerSelectBytes = 24 * 1024;
+// Most problems per layer run that the one-workgroup-per-problem kernels select for together.
+constexpr int kOwnerMaxLayer = 16;
 // Rows copied by one workgroup of the compaction kernels.
 constexpr int kGatherRows = 64;
 // Most kept rows per problem when slots go by score rank (their order keys are held
@@ -50,7 +54,15 @@ struct LaunchParams {
   uint32_t lds_bytes;          // dynamic LDS of the launch
   // re-positioning inside the one-workgroup-per-problem kernels (ascending slots)
   int32_t rope_pairing;        // FINCH_ROPE_OFF / _HALF / _INTERLEAVED
+  int32_t rank_order;          // kept rows go to the slot of their score's rank (else ascending slots)
   double rope_log2_base;       // log2 of the rotary base
+  // layer-wise selection inside the one-workgroup-per-problem kernels: the L workgroups of
+  // a run of problems meet through two counters per run (scores out / scores read) and
+  // share one error word behind them; zeroed before the launch
+  int32_t layer_group;         // L (1: every problem selects for itself)
+  int32_t* layer_sync;         // [2 * runs]
+  int32_t* layer_err;          // one word behind them
+  int64_t spin_ticks;          // longest wait for the other workgroups, in 100 MHz ticks
 };
 
 // Launchers; each returns hipGetLastError() after the launch.
@@ -72,6 +84,7 @@ hipError_t launch_owner_bf16(int head_dim, const LaunchParams& p, int stages, hi
 hipError_t launch_owner_loop_bf16(int head_dim, const LaunchParams& p, const int* step_first,
                                   int n_steps, int n_slots, hipStream_t s);
 hipError_t set_max_lds_owner(size_t bytes);
+hipError_t launch_zero_words(int32_t* words, int n, int32_t* one_more, hipStream_t s);
 // the same with rows of the chunk's own tokens (desc.q_doc)
 hipError_t launch_owner_doc_bf16(int head_dim, const LaunchParams& p, int stages, hipStream_t s);
 hipError_t launch_owner_loop_doc_bf16(int head_dim, const LaunchParams& p, const int* step_first,

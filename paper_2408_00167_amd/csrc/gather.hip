@@ -71,4 +71,21 @@ hipError_t launch_gather(const LaunchParams& p, int row_bytes, int r_max, hipStr
   return hipGetLastError();
 }
 
+namespace {
+__global__ void zero_words(int32_t* w, int n, int32_t* one_more) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) w[i] = 0;
+  if (i == 0 && one_more) *one_more = 0;
+}
+}  // namespace
+
+// Clears `n` words at `words` and the word at `one_more` (may be null) with a small kernel
+// (a plain fill: safe inside a captured graph, where memset nodes are not).
+hipError_t launch_zero_words(int32_t* words, int n, int32_t* one_more, hipStream_t s) {
+  if (n <= 0 && !one_more) return hipSuccess;
+  const int blocks = n > 0 ? (n + 255) / 256 : 1;
+  hipLaunchKernelGGL(zero_words, dim3(blocks), dim3(256), 0, s, words, n, one_more);
+  return hipGetLastError();
+}
+
 }  // namespace finch

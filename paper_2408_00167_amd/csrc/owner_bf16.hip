@@ -11,7 +11,7 @@ size_t owner_lds_bytes(int head_dim, int row_chunk) {
   // and the selection scratch with room for about 6000 kept indices
   const size_t q = static_cast<size_t>(row_chunk) * (head_dim * 2 + 16);
   const size_t scoring = static_cast<size_t>(row_chunk) * (kOwnWaves * 8 + 4) + 16;
-  const size_t selection = sizeof(SelLds) + 24 * 1024;
+  const size_t selection = sizeof(SelLds) + kOwnerSelectBytes;
   return q + (scoring > selection ? scoring : selection);
 }
 

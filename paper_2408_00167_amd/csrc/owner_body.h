@@ -39,10 +39,10 @@ __device__ __forceinline__ int own_next_block(int* counter, int lane) {
   return __builtin_amdgcn_readfirstlane(v);
 }
 
-// Copy rows idx[0..r) of [cache ; chunk] of K and V into k_out / v_out.  `lidx`
-// (LDS) or `gidx` (memory, written by this workgroup) holds the indices; with
-// `identity` row t is simply candidate t.
-template <int SEGS>
+// Copy rows idx[0..r) of [cache ; chunk] of K and V into k_out / v_out by NT threads
+// (`tid` = index among them).  `lidx` (LDS) or `gidx` (memory, written by this
+// workgroup) holds the indices; with `identity` row t is simply candidate t.
+template <int SEGS, int NT = kOwnThreads>
 __device__ __forceinline__ void own_gather(const finch_problem& pb, int N, int r, const int* lidx,
                                            const FINCH_GLOBAL int* gidx, bool identity, int tid) {
   const FINCH_GLOBAL u32x4* kc = as_global<u32x4>(pb.k_cache);
@@ -51,7 +51,7 @@ __device__ __forceinline__ void own_gather(const finch_problem& pb, int N, int r
   const FINCH_GLOBAL u32x4* vk = as_global<u32x4>(pb.v_chunk);
   FINCH_GLOBAL u32x4* ko = as_global_mut<u32x4>(pb.k_out);
   FINCH_GLOBAL u32x4* vo = as_global_mut<u32x4>(pb.v_out);
-  constexpr int kRowsPerIter = kOwnThreads / SEGS;
+  constexpr int kRowsPerIter = NT / SEGS;
   constexpr int kUnroll = 8;
   const int seg = tid % SEGS, sub = tid / SEGS;
   for (int row0 = 0; row0 < r; row0 += kRowsPerIter * kUnroll) {
@@ -77,13 +77,16 @@ __device__ __forceinline__ void own_gather(const finch_problem& pb, int N, int r
   }
 }
 
-// The same with the kept keys re-positioned to their (ascending) slots: row t is
-// turned by t - idx[t] positions while it is copied.  A thread owns two pieces of
-// a row, d/2 channels apart, i.e. both partners of its channel pairs.
-template <int SEGS>
+// The same with the kept keys re-positioned: slot p takes kept row t = p (the ascending
+// order), or, with `ranked` (LDS; see own_rank_kept), the kept row whose record stands
+// at place p of the sorted records; the key is turned by p - idx[t] positions while it
+// is copied (not at all with pairing FINCH_ROPE_OFF).  A thread owns two pieces of a
+// row, d/2 channels apart, i.e. both partners of its channel pairs.
+template <int SEGS, int NT = kOwnThreads>
 __device__ __forceinline__ void own_gather_rot(const finch_problem& pb, int N, int r, const int* lidx,
                                                const FINCH_GLOBAL int* gidx, bool identity, int pairing,
-                                               double log2_base, int tid) {
+                                               double log2_base, int tid,
+                                               const unsigned long long* ranked = nullptr) {
   constexpr int kHalf = SEGS / 2, E = 8;
   const FINCH_GLOBAL u32x4* kc = as_global<u32x4>(pb.k_cache);
   const FINCH_GLOBAL u32x4* kk = as_global<u32x4>(pb.k_chunk);
@@ -91,20 +94,22 @@ __device__ __forceinline__ void own_gather_rot(const finch_problem& pb, int N, i
   const FINCH_GLOBAL u32x4* vk = as_global<u32x4>(pb.v_chunk);
   FINCH_GLOBAL u32x4* ko = as_global_mut<u32x4>(pb.k_out);
   FINCH_GLOBAL u32x4* vo = as_global_mut<u32x4>(pb.v_out);
-  constexpr int kRowsPerIter = kOwnThreads / kHalf;
+  constexpr int kRowsPerIter = NT / kHalf;
   constexpr int kUnroll = 4;
   const int seg = tid % kHalf, sub = tid / kHalf;
   double th[E];
   pair_thetas<E, kHalf>(pairing, seg, log2_base, th);
   for (int row0 = 0; row0 < r; row0 += kRowsPerIter * kUnroll) {
     u32x4 ka[kUnroll], kb[kUnroll], va[kUnroll], vb[kUnroll];
-    int shift[kUnroll];
+    int shift[kUnroll], slot[kUnroll];
 #pragma unroll
     for (int it = 0; it < kUnroll; ++it) {
-      const int t = min(row0 + it * kRowsPerIter + sub, r - 1);
+      const int p = min(row0 + it * kRowsPerIter + sub, r - 1);
+      const int t = ranked ? min(static_cast<int>(~static_cast<unsigned>(ranked[p])), r - 1) : p;
       int j = identity ? t : (lidx ? lidx[t] : gidx[t]);
       j = min(max(j, 0), N - 1);
-      shift[it] = t - j;
+      slot[it] = p;
+      shift[it] = p - j;
       const bool cached = j < pb.c;
       const size_t off = static_cast<size_t>(cached ? j : j - pb.c) * SEGS + seg;
       ka[it] = (cached ? kc : kk)[off];
@@ -114,10 +119,9 @@ __device__ __forceinline__ void own_gather_rot(const finch_problem& pb, int N, i
     }
 #pragma unroll
     for (int it = 0; it < kUnroll; ++it) {
-      const int t = row0 + it * kRowsPerIter + sub;
-      if (t < r) {
-        if (shift[it] != 0) rotate_pieces<E>(pairing, th, shift[it], ka[it], kb[it]);
-        const size_t o = static_cast<size_t>(t) * SEGS + seg;
+      if (row0 + it * kRowsPerIter + sub < r) {
+        if (pairing != FINCH_ROPE_OFF && shift[it] != 0) rotate_pieces<E>(pairing, th, shift[it], ka[it], kb[it]);
+        const size_t o = static_cast<size_t>(slot[it]) * SEGS + seg;
         ko[o] = ka[it];
         ko[o + kHalf] = kb[it];
         vo[o] = va[it];
@@ -129,6 +133,40 @@ __device__ __forceinline__ void own_gather_rot(const finch_problem& pb, int N, i
 
 }  // namespace
 
+// Kept rows by relevance: one 64-bit record per kept row t < r - order key of its score
+// in the upper half, ~t in the lower - sorted in descending order by a bitonic network
+// over the next power of two (padding records are zero and end up last), so that place
+// p holds the row with the p-th highest score, equal scores in index order.  `ranked`
+// needs 8 * 2^ceil(log2 r) bytes of LDS.  Whole workgroup; ends with a barrier.
+__device__ __forceinline__ void own_rank_kept(unsigned long long* ranked, int r, const FINCH_GLOBAL float* scores,
+                                              const int* lidx, bool identity, int tid) {
+  int npad = 2;
+  while (npad < r) npad <<= 1;
+  for (int u = tid; u < npad; u += kOwnThreads) {
+    unsigned long long rec = 0ull;
+    if (u < r)
+      rec = (static_cast<unsigned long long>(order_key(scores[identity ? u : lidx[u]])) << 32) | static_cast<unsigned>(~u);
+    ranked[u] = rec;
+  }
+  __syncthreads();
+  for (int k = 2; k <= npad; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int i = tid; i < npad; i += kOwnThreads) {
+        const int x = i ^ j;
+        if (x > i) {
+          const unsigned long long a = ranked[i], b = ranked[x];
+          const bool descending = (i & k) == 0;
+          if (descending ? a < b : a > b) {
+            ranked[i] = b;
+            ranked[x] = a;
+          }
+        }
+      }
+      __syncthreads();
+    }
+  }
+}
+
 // One step of one problem by the whole workgroup.  QBT = row blocks (of 32 prompt
 // rows) per pass over the keys the code is compiled for; prm.row_chunk <= 32 * QBT.
 // stages: 0 = scores only, 1 = scores, top-r and compaction.  `staged_q` names the
@@ -137,12 +175,20 @@ __device__ __forceinline__ void own_gather_rot(const finch_problem& pb, int N, i
 // count mean the same rows and the copy is skipped.  Ends with every thread past
 // its last access to LDS only after the next barrier: callers that go on to
 // another step must put a barrier in between.
+// With prm.layer_group = L > 1 the L workgroups of a run of slots (a layer's KV heads)
+// select together (Method: "Sum over heads", then one top-r per layer): each publishes
+// its scores, waits for the others (bounded: a wait that runs out sets the error word
+// and the workgroup goes on with what it finds), adds the L vectors up in the same order
+// and selects on the sum, so that all L arrive at the same indices on their own.
+// `step_probs` are the descriptors of this step, `epoch` counts the exchanges this
+// workgroup has been through in this launch; returns true if the step made one.
 template <int D, int QBT, bool ROT, bool DOC>
-__device__ __forceinline__ void own_step_body(const LaunchParams& prm, const finch_problem& pb, int slot,
+__device__ __forceinline__ bool own_step_body(const LaunchParams& prm, const finch_problem& pb, int slot,
                                               int stages, char* smem, const void*& staged_q,
-                                              int& staged_rows) {
+                                              int& staged_rows, const finch_problem* step_probs = nullptr,
+                                              int epoch = 0) {
   const int N = pb.c + pb.m;
-  if (N == 0) return;
+  if (N == 0) return false;
   const int Rp = (DOC && !pb.q) ? 0 : prm.group * pb.n_que;  // prompt rows
   // (the thread index goes through an empty asm: in the whole-loop kernel the compiler
   // would otherwise compute everything that depends only on it once for all steps and
@@ -162,6 +208,24 @@ __device__ __forceinline__ void own_step_body(const LaunchParams& prm, const fin
   const float sc = prm.scale_log2;
   float* gscores = pb.scores ? pb.scores : prm.ws_scores + static_cast<size_t>(slot) * prm.score_stride;
   FINCH_GLOBAL float* dst = as_global_mut<float>(gscores);
+  const int L = prm.layer_group;
+  const bool layered = stages && L > 1 && pb.r > 0 && pb.r < N;  // the same in every workgroup of the run
+  int* const sync_words = (stages && L > 1) ? prm.layer_sync + 2 * (slot / L) : nullptr;
+  if (sync_words && epoch > 0) {
+    // nobody of the run may still be adding up the scores of the step before when this
+    // step's scores start to overwrite them
+    if (tid == 0) {
+      const long long t0 = wall_clock64();
+      while (__hip_atomic_load(sync_words + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < L * epoch) {
+        __builtin_amdgcn_s_sleep(8);
+        if (wall_clock64() - t0 > prm.spin_ticks) {
+          atomicOr(prm.layer_err, 1);
+          break;
+        }
+      }
+    }
+    __syncthreads();
+  }
 
   // Row chunks: the prompt rows first (they see every key, so they initialise all
   // scores), then, in DOC kernels, the rows of the chunk's own tokens, head by head
@@ -363,7 +427,12 @@ __device__ __forceinline__ void own_step_body(const LaunchParams& prm, const fin
         }
         const float tot = fold16_over32(u, t);
         const int key = kbase + acc_key(t >> 1, h);
-        if ((t & 1) == 0 && key < N) dst[key] = first_chunk ? tot : dst[key] + tot;
+        if ((t & 1) == 0 && key < N) {
+          const float val = first_chunk ? tot : dst[key] + tot;
+          // (scores other workgroups will read go out past this compute unit's caches)
+          if (layered) __hip_atomic_store(gscores + key, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          else dst[key] = val;
+        }
       };
       if (b >= 0) {
         while (true) {
@@ -385,11 +454,11 @@ __device__ __forceinline__ void own_step_body(const LaunchParams& prm, const fin
   // what the prompt-row region of LDS holds now (selection scratch lies behind it)
   staged_q = (n_chunks == 1) ? pb.q : nullptr;
   staged_rows = Rp;
-  if (!stages) return;
+  if (!stages) return false;
 
   // ---- top-r on the scores this workgroup has just written
   const int r = min(pb.r, N);
-  if (r <= 0) return;
+  if (r <= 0) return false;
   FINCH_GLOBAL int* gidx = as_global_mut<int>(pb.idx);
   const bool identity = r >= N;
   // selection scratch: behind the staged prompt rows (pass-1 statistics are dead)
@@ -405,26 +474,76 @@ __device__ __forceinline__ void own_step_body(const LaunchParams& prm, const fin
       lidx = reinterpret_cast<int*>(sel + used);
       used += static_cast<size_t>(r) * 4;
     }
+    if (layered) {
+      // this workgroup's scores are out (stored past the caches, and every thread has waited
+      // for its own stores at the barrier after pass 2); wait until all L workgroups of the
+      // run say the same
+      const int run = slot / L;
+      if (tid == 0) {
+        __hip_atomic_fetch_add(sync_words, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const long long t0 = wall_clock64();
+        while (__hip_atomic_load(sync_words, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < L * (epoch + 1)) {
+          __builtin_amdgcn_s_sleep(8);
+          if (wall_clock64() - t0 > prm.spin_ticks) {
+            atomicOr(prm.layer_err, 1);
+            break;
+          }
+        }
+      }
+      if (tid < L) {
+        const finch_problem pg = step_probs[run * L + tid];
+        fl->layer_src[tid] = pg.scores ? pg.scores
+                                       : prm.ws_scores + static_cast<size_t>(run * L + tid) * prm.score_stride;
+      }
+      __syncthreads();
+    }
+    const LayerScores layer_sum = {fl->layer_src, L};
+    const OneScoreVector own = {dst};
     if (N <= kOwnThreads * kSelRegKeys) {
-      select_regs<kOwnThreads>(dst, N, r, gidx, lidx, fl, tid, lane, wave);
+      if (layered) select_regs<kOwnThreads>(layer_sum, N, r, gidx, lidx, fl, tid, lane, wave);
+      else select_regs<kOwnThreads>(own, N, r, gidx, lidx, fl, tid, lane, wave);
     } else {
       unsigned* lkeys = nullptr;
       if (used + static_cast<size_t>(N) * 4 <= sel_bytes) {
         lkeys = reinterpret_cast<unsigned*>(sel + used);
-        for (int i = tid; i < N; i += kOwnThreads) lkeys[i] = order_key(dst[i]);
+        for (int i = tid; i < N; i += kOwnThreads) lkeys[i] = order_key(layered ? layer_sum(i) : own(i));
       }
       __syncthreads();
-      select_generic<kOwnThreads>(lkeys, dst, N, r, gidx, lidx, fl, tid, lane, wave);
+      if (layered) select_generic<kOwnThreads>(lkeys, layer_sum, N, r, gidx, lidx, fl, tid, lane, wave);
+      else select_generic<kOwnThreads>(lkeys, own, N, r, gidx, lidx, fl, tid, lane, wave);
     }
     __syncthreads();  // idx (LDS and memory) complete
+    // (the other workgroups' scores have been read for the last time)
+    if (layered && tid == 0) __hip_atomic_fetch_add(sync_words + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 
   // ---- compaction
   if (ROT) {
-    own_gather_rot<D / 8>(pb, N, r, lidx, gidx, identity, prm.rope_pairing, prm.rope_log2_base, tid);
+    // slots by relevance (Method: Managing the Cache, the worked example): the rank of a kept
+    // row's score among the kept ones, highest first, equal scores by index.  The host
+    // sends such batches here only if the indices and the records of all kept rows fit
+    // behind the selection scratch.
+    unsigned long long* ranked = nullptr;
+    if (prm.rank_order) {
+      __syncthreads();  // (the identity case has not been through a barrier since the scores)
+      ranked = reinterpret_cast<unsigned long long*>(sel + sizeof(SelLds) + ((static_cast<size_t>(r) * 4 + 7) & ~size_t{7}));
+      own_rank_kept(ranked, r, dst, lidx, identity, tid);
+    }
+    own_gather_rot<D / 8>(pb, N, r, lidx, gidx, identity, prm.rope_pairing, prm.rope_log2_base, tid, ranked);
   } else {
     own_gather<D / 8>(pb, N, r, lidx, gidx, identity, tid);
   }
+  return layered;
+}
+
+// Which slot workgroup b of n takes.  Normally b itself.  With layer groups the L
+// workgroups of a run exchange their scores, so runs are kept on one of the chip's eight
+// dies (workgroups go to the dies in turn: b % 8) and the exchange stays in that die's L2:
+// die x takes the slots [x * (n / 8) + min(x, n % 8), ...) in the order of its workgroups.
+__device__ __forceinline__ int own_slot_of(int b, int n, int L) {
+  if (L <= 1) return b;
+  const int x = b & 7, j = b >> 3;
+  return x * (n >> 3) + min(x, n & 7) + j;
 }
 
 // One launch = one step of every problem of a batch; workgroup b owns problem b.
@@ -432,11 +551,11 @@ __device__ __forceinline__ void own_step_body(const LaunchParams& prm, const fin
 template <int D, int QBT, bool ROT, bool DOC>
 __global__ __launch_bounds__(kOwnThreads) void owner_step_bf16(LaunchParams prm, int stages) {
   extern __shared__ __align__(16) char smem[];
-  const int p = blockIdx.x;
+  const int p = own_slot_of(blockIdx.x, gridDim.x, stages ? prm.layer_group : 1);
   const finch_problem pb = prm.probs[p];
   const void* staged_q = nullptr;
   int staged_rows = 0;
-  own_step_body<D, QBT, ROT, DOC>(prm, pb, p, stages, smem, staged_q, staged_rows);
+  own_step_body<D, QBT, ROT, DOC>(prm, pb, p, stages, smem, staged_q, staged_rows, prm.probs, 0);
 }
 
 // One launch = the whole chunk loop (Method: Document Segmentation): workgroup b
@@ -448,14 +567,17 @@ template <int D, int QBT, bool ROT, bool DOC>
 __global__ __launch_bounds__(kOwnThreads) void owner_loop_bf16(LaunchParams prm, const int* step_first,
                                                                int n_steps) {
   extern __shared__ __align__(16) char smem[];
-  const int slot = blockIdx.x;
+  const int slot = own_slot_of(blockIdx.x, gridDim.x, prm.layer_group);
   const void* staged_q = nullptr;
   int staged_rows = 0;
+  int epoch = 0;
   for (int s = 0; s < n_steps; ++s) {
     const int first = step_first[s];
     if (slot >= step_first[s + 1] - first) break;  // slots are filled from the front
     const finch_problem pb = prm.probs[first + slot];
-    own_step_body<D, QBT, ROT, DOC>(prm, pb, slot, /*stages=*/1, smem, staged_q, staged_rows);
+    if (own_step_body<D, QBT, ROT, DOC>(prm, pb, slot, /*stages=*/1, smem, staged_q, staged_rows, prm.probs + first,
+                                        epoch))
+      ++epoch;
     // the rows this step wrote are the next step's cache: complete before it reads
     __syncthreads();
   }
@@ -505,7 +627,7 @@ template <bool DOC>
 hipError_t launch_owner_impl(int head_dim, const LaunchParams& p, int stages, hipStream_t s) {
   if (p.n_problems <= 0) return hipSuccess;
   const dim3 grid(static_cast<unsigned>(p.n_problems)), block(kOwnThreads);
-  const bool ok = with_step_kernel<DOC>(head_dim, own_qbt(p.row_chunk), p.rope_pairing != FINCH_ROPE_OFF,
+  const bool ok = with_step_kernel<DOC>(head_dim, own_qbt(p.row_chunk), p.rope_pairing != FINCH_ROPE_OFF || p.rank_order,
                                         [&](auto kern) {
                                           hipLaunchKernelGGL(kern, grid, block, p.lds_bytes, s, p, stages);
                                         });
@@ -519,7 +641,7 @@ hipError_t launch_owner_loop_impl(int head_dim, const LaunchParams& p, const int
                                   int n_slots, hipStream_t s) {
   if (n_slots <= 0 || n_steps <= 0) return hipSuccess;
   const dim3 grid(static_cast<unsigned>(n_slots)), block(kOwnThreads);
-  const bool ok = with_loop_kernel<DOC>(head_dim, own_qbt(p.row_chunk), p.rope_pairing != FINCH_ROPE_OFF,
+  const bool ok = with_loop_kernel<DOC>(head_dim, own_qbt(p.row_chunk), p.rope_pairing != FINCH_ROPE_OFF || p.rank_order,
                                         [&](auto kern) {
                                           hipLaunchKernelGGL(kern, grid, block, p.lds_bytes, s, p, step_first,
                                                              n_steps);

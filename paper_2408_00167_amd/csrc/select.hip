@@ -24,9 +24,9 @@ __global__ __launch_bounds__(kSelThreads) void select_topr(LaunchParams prm) {
     return;
   }
   if (N <= kSelThreads * kSelRegKeys) {
-    select_regs<kSelThreads>(scores, N, r, idx, nullptr, &lds, tid, lane, wave);
+    select_regs<kSelThreads>(OneScoreVector{scores}, N, r, idx, nullptr, &lds, tid, lane, wave);
   } else {
-    select_generic<kSelThreads>(nullptr, scores, N, r, idx, nullptr, &lds, tid, lane, wave);
+    select_generic<kSelThreads>(nullptr, OneScoreVector{scores}, N, r, idx, nullptr, &lds, tid, lane, wave);
   }
 }
 
@@ -63,9 +63,9 @@ __global__ __launch_bounds__(kSelThreads) void select_layer(LaunchParams prm, in
   __syncthreads();  // the sums this workgroup wrote are read back by other threads below
   FINCH_GLOBAL int* idx0 = as_global_mut<int>(pb0.idx);
   if (N <= kSelThreads * kSelRegKeys) {
-    select_regs<kSelThreads>(total, N, r, idx0, nullptr, &lds, tid, lane, wave);
+    select_regs<kSelThreads>(OneScoreVector{total}, N, r, idx0, nullptr, &lds, tid, lane, wave);
   } else {
-    select_generic<kSelThreads>(nullptr, total, N, r, idx0, nullptr, &lds, tid, lane, wave);
+    select_generic<kSelThreads>(nullptr, OneScoreVector{total}, N, r, idx0, nullptr, &lds, tid, lane, wave);
   }
   __syncthreads();
   for (int g = 1; g < group; ++g) {

@@ -38,10 +38,38 @@ __device__ __forceinline__ int wave_inclusive_scan(int x) {
   return v;
 }
 
+constexpr int kSelMaxLayer = 16;  // most score vectors a selection inside a workgroup adds up
+
 struct SelLds {  // LDS scratch of a selection
   int hist[4][256];
   int wave_tot[2][kSelMaxWaves];
   int digit[4], remaining[4];
+  const float* layer_src[kSelMaxLayer];  // LayerScores: the score vectors of a layer's heads
+};
+
+// Where a selection takes the score of candidate i from: one vector ...
+struct OneScoreVector {
+  const FINCH_GLOBAL float* p;
+  __device__ __forceinline__ float operator()(int i) const { return p[i]; }
+};
+// ... or the sum of the L vectors of a layer's heads, added head by head in fp32 (Method:
+// "Sum over heads"; the order is that of select_layer, so both give the same bits).  The
+// vectors come from other workgroups: they are read past this compute unit's caches.
+struct LayerScores {
+  const float* const* src;  // LDS table of L pointers
+  int L;
+  __device__ __forceinline__ float operator()(int i) const {
+    // all loads first (they come from far away), then the sum in head order
+    float v[kSelMaxLayer];
+#pragma unroll
+    for (int g = 0; g < kSelMaxLayer; ++g)
+      v[g] = g < L ? __hip_atomic_load(src[g] + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
+    float t = v[0];
+#pragma unroll
+    for (int g = 1; g < kSelMaxLayer; ++g)
+      if (g < L) t = t + v[g];
+    return t;
+  }
 };
 
 // Wave 0 only: lane L owns bins 4L..4L+3 of `hist`; finds the bin where the count
@@ -110,14 +138,14 @@ __device__ __forceinline__ int sel_block_scan(int v, int* wave_tot, int lane, in
   return base + incl - v;
 }
 
-// Any N.  `keys` is LDS (order keys staged there) or nullptr (scores re-read from
-// memory each round).  Writes idx to `gidx` and, if `lidx` is not null, also to
+// Any N.  `keys` is LDS (order keys staged there) or nullptr (scores taken from
+// `score_of` again each round).  Writes idx to `gidx` and, if `lidx` is not null, also to
 // LDS.  0 < r < N.  Whole workgroup; starts and ends without a barrier.
-template <int NT>
-__device__ __forceinline__ void select_generic(const unsigned* keys, const FINCH_GLOBAL float* gscores,
+template <int NT, class Src = OneScoreVector>
+__device__ __forceinline__ void select_generic(const unsigned* keys, const Src& score_of,
                                                int N, int r, FINCH_GLOBAL int* gidx, int* lidx, SelLds* f,
                                                int tid, int lane, int wave) {
-  auto key_at = [&](int i) -> unsigned { return keys ? keys[i] : order_key(gscores[i]); };
+  auto key_at = [&](int i) -> unsigned { return keys ? keys[i] : order_key(score_of(i)); };
   unsigned prefix = 0, mask = 0;
   int remaining = r;
   int* hist = f->hist[0];
@@ -164,8 +192,8 @@ __device__ __forceinline__ void select_generic(const unsigned* keys, const FINCH
 // as the wave's first active lane are counted with one atomic) and the ordered
 // output needs two workgroup scans.  0 < r < N.  Whole workgroup; starts with a
 // barrier of its own and ends without one.
-template <int NT>
-__device__ __forceinline__ void select_regs(const FINCH_GLOBAL float* gscores, int N, int r,
+template <int NT, class Src = OneScoreVector>
+__device__ __forceinline__ void select_regs(const Src& score_of, int N, int r,
                                             FINCH_GLOBAL int* gidx, int* lidx, SelLds* f, int tid,
                                             int lane, int wave) {
   const int K = (N + NT - 1) / NT;
@@ -173,7 +201,7 @@ __device__ __forceinline__ void select_regs(const FINCH_GLOBAL float* gscores, i
   const int nk = max(0, min(K, N - i0));  // candidates of this thread
   unsigned key[kSelRegKeys];
 #pragma unroll
-  for (int k = 0; k < kSelRegKeys; ++k) key[k] = k < nk ? order_key(gscores[i0 + k]) : 0u;
+  for (int k = 0; k < kSelRegKeys; ++k) key[k] = k < nk ? order_key(score_of(i0 + k)) : 0u;
   for (int i = tid; i < 4 * 256; i += NT) (&f->hist[0][0])[i] = 0;
   __syncthreads();
   unsigned prefix = 0, mask = 0;

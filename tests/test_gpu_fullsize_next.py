@@ -80,17 +80,20 @@ def validate_layer_loop(loop, heads, what):
 
 
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("per_step", [False, True])
-def test_c4_layer_wise_selection_whole_loop(per_step):
-    """One layer of C4 (8 KV heads, one selection per step for all of them) through all 32
-    chunk steps."""
-    say(f"C4 layer-wise selection, per_step={per_step}")
+@pytest.mark.parametrize("per_step,path", [(False, "separate"), (True, "separate"), (False, "owner"), (True, "owner")])
+def test_c4_layer_wise_selection_whole_loop(per_step, path):
+    """Two layers of C4 (8 KV heads each, one selection per step for all of them) through
+    all 32 chunk steps: one kernel per stage, or one workgroup per problem (whole loop
+    in one launch, or step by step) with the layer's workgroups exchanging their scores."""
+    say(f"C4 layer-wise selection, per_step={per_step} {path}")
     w, probs = c4_problems(16)      # two layers' worth of heads: two runs of 8
     fin = F.Finch(F.FINCH_BF16, 128, 4)
+    fin.set_step_path(F.FINCH_PATH_OWNER if path == "owner" else F.FINCH_PATH_SEPARATE)
     F.finch_set_option(fin.ctx, F.FINCH_OPT_LAYER_GROUP, 8)
     loop = ChunkLoop(fin, probs, w.chunk, history=True)
     assert loop.n_steps == 32
     loop.run(per_step=per_step)
+    assert fin.workspace_status() == 0
     for run in range(2):
         st = validate_layer_loop(loop, list(range(8 * run, 8 * run + 8)), f"C4 layer run {run}")
         say(f"  run {run}: {st}")
@@ -98,17 +101,18 @@ def test_c4_layer_wise_selection_whole_loop(per_step):
 
 
 @pytest.mark.timeout(900)
-def test_c4_repositioned_whole_loop():
-    """Keys rotated to their (ascending) slots while they are compacted, rotary pairs d/2
-    apart, all 32 steps: step by step with the cache the GPU holds read back after every
-    step and every step against the oracle, then the whole loop in one launch, which must
-    give the same bits."""
-    say("C4 re-positioning")
+@pytest.mark.parametrize("order", ["ascending", "rank"])
+def test_c4_repositioned_whole_loop(order):
+    """Keys rotated to their slots (ascending, or by relevance as in the paper's worked
+    example) while they are compacted, rotary pairs d/2 apart, all 32 steps: step by step
+    with the cache the GPU holds read back after every step and every step against the
+    oracle, then the whole loop in one launch, which must give the same bits."""
+    say(f"C4 re-positioning, {order} slots")
     base = 500000.0
     w, probs = c4_problems(4)
     fin = F.Finch(F.FINCH_BF16, 128, 4)
     fin.set_step_path(F.FINCH_PATH_OWNER)
-    fin.set_reposition(F.FINCH_ROPE_HALF, F.FINCH_ORDER_ASCENDING, base)
+    fin.set_reposition(F.FINCH_ROPE_HALF, F.FINCH_ORDER_RANK if order == "rank" else F.FINCH_ORDER_ASCENDING, base)
     a = ChunkLoop(fin, probs, w.chunk, history=True)
     check = [0, 3]
     caches = {p: (np.zeros((0, 128), np.uint16), np.zeros((0, 128), np.uint16)) for p in check}
@@ -130,7 +134,7 @@ def test_c4_repositioned_whole_loop():
             H.check_indices(idx, want, r, f"reposition problem {p} step {i}")
             o = a.cap_off[p]
             t = dict(k_out=a.kbuf[side][o:o + r], v_out=a.vbuf[side][o:o + r], scores=g_scores, c=Kc.shape[0], m=hi - lo)
-            worst_rot = max(worst_rot, H.check_repositioned(t, Kc, Kk, Vc, Vk, idx, r, "half", "ascending", base,
+            worst_rot = max(worst_rot, H.check_repositioned(t, Kc, Kk, Vc, Vk, idx, r, "half", order, base,
                                                             f"reposition problem {p} step {i}"))
             caches[p] = (W.to_numpy_storage(a.kbuf[side][o:o + r]).copy(), W.to_numpy_storage(a.vbuf[side][o:o + r]).copy())
     say(f"  step by step ok, worst rotation error (relative to the row maximum) {worst_rot:.2e}")

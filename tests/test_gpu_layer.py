@@ -57,19 +57,25 @@ def validate_layers(ts, L, what):
     return swaps
 
 
-@pytest.mark.parametrize("dtype,d,group,L", [(torch.bfloat16, 128, 4, 8), (torch.bfloat16, 64, 1, 3),
-                                             (torch.float32, 64, 1, 2)])
-def test_layer_wise_selection(dtype, d, group, L):
-    say(f"layer-wise {dtype} d={d} G={group} L={L}")
+@pytest.mark.parametrize("dtype,d,group,L,path", [(torch.bfloat16, 128, 4, 8, "separate"), (torch.bfloat16, 64, 1, 3, "separate"),
+                                                  (torch.float32, 64, 1, 2, "separate"),
+                                                  (torch.bfloat16, 128, 4, 8, "owner"), (torch.bfloat16, 64, 1, 3, "owner"),
+                                                  (torch.bfloat16, 128, 2, 16, "owner")])
+def test_layer_wise_selection(dtype, d, group, L, path):
+    """One kernel per stage (the layer's scores summed by the selection kernel), or one
+    workgroup per problem (the L workgroups of a layer wait for each other's scores)."""
+    say(f"layer-wise {dtype} d={d} G={group} L={L} {path}")
     fin = F.Finch(H.finch_dtype(torch.empty(0, dtype=dtype)), d, group)
+    fin.set_step_path(F.FINCH_PATH_OWNER if path == "owner" else F.FINCH_PATH_SEPARATE)
     F.finch_set_option(fin.ctx, F.FINCH_OPT_LAYER_GROUP, L)
     layers = LAYERS if dtype == torch.bfloat16 else [dict(s, n_que=min(s["n_que"], 8), m=min(s["m"], 1200)) for s in LAYERS]
     specs = [sp for sp in layers for _ in range(L)]
     b1, t1 = H.single_step_case(fin, specs, dtype, d, group, seed=900 + L)
     fin.step(b1)
     say(f"  swaps {validate_layers(t1, L, 'step')}")
+    assert fin.workspace_status() == 0
     b2, t2 = H.single_step_case(fin, specs, dtype, d, group, seed=900 + L)
-    fin.score(b2); fin.topk(b2); fin.compact(b2)
+    fin.score(b2); fin.topk(b2); fin.compact(b2)      # (top-r and compaction alone always run per stage)
     torch.cuda.synchronize()
     for a, b in zip(t1, t2):
         for name in ("scores", "idx", "k_out", "v_out"):
@@ -93,9 +99,18 @@ def test_layer_group_argument_checks():
             fin.step(batch)
         assert e.value.status == F.FINCH_ERR_INVALID_ARG
     batch, ts = H.single_step_case(fin, [sp] * 4, torch.bfloat16, 128, 4, seed=2)
+    # one workgroup per problem: only while a layer's workgroups fit on the chip together
+    # and the layer has at most 16 heads
     fin.set_step_path(F.FINCH_PATH_OWNER)
+    F.finch_set_option(fin.ctx, F.FINCH_OPT_LAYER_GROUP, 32)
+    b32, _ = H.single_step_case(fin, [sp] * 32, torch.bfloat16, 128, 4, seed=2)
     with pytest.raises(F.FinchError) as e:
-        fin.step(batch)
+        fin.step(b32)
+    assert e.value.status == F.FINCH_ERR_UNSUPPORTED
+    F.finch_set_option(fin.ctx, F.FINCH_OPT_LAYER_GROUP, 2)
+    many, _ = H.single_step_case(fin, [sp] * 600, torch.bfloat16, 128, 4, seed=2)
+    with pytest.raises(F.FinchError) as e:
+        fin.step(many)
     assert e.value.status == F.FINCH_ERR_UNSUPPORTED
     fin.set_step_path(F.FINCH_PATH_AUTO)
     fin.set_reposition(F.FINCH_ROPE_HALF, F.FINCH_ORDER_RANK, 1e4)
