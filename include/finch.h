@@ -125,9 +125,9 @@ finch_status finch_prompt_lse(finch_ctx* ctx, const finch_problem* host_desc,
  * those, and the normalisation step multiplies them by (c + i + 1) / (c + m) - read
  * per row: the factor offsets the thinner spread of rows that see more keys and is
  * 1 for prompt rows.  scores[j] is the sum over all rows that see key j.  desc.q
- * may then be NULL (document rows only; n_que is ignored).  bf16 only, and always
- * through the one-workgroup-per-problem kernels whatever the batch size; the work
- * grows from G*n_que to G*(n_que + m) rows per problem. */
+ * may then be NULL (document rows only; n_que is ignored).  Always through the
+ * one-workgroup-per-problem kernels whatever the batch size (FINCH_PATH_SEPARATE:
+ * FINCH_ERR_UNSUPPORTED); the work grows from G*n_que to G*(n_que + m) rows per problem. */
 
 /* Selection (Method: t = top-r(A_agg, r)): reads desc.scores (any finite fp32),
  * writes the indices of the min(r, c+m) largest into desc.idx in ascending order;
@@ -253,11 +253,12 @@ finch_status finch_schedule_mode(int64_t n_cont, int32_t m, int64_t k, int32_t m
 
 /* Options.  FINCH_OPT_STEP_PATH picks how the stages are launched.  SEPARATE uses
  * one kernel per stage: row statistics, merge, per-key sums, top-r, compaction.
- * OWNER (bf16 only) gives every problem to one workgroup of 8 waves that runs all
- * stages of the step - or, in finch_loop, of all steps - back to back with nothing
- * exchanged between workgroups; batches it cannot run fail with
- * FINCH_ERR_UNSUPPORTED.  AUTO (default) takes OWNER when the batch has enough
- * problems to fill the chip's compute units in whole rounds, else SEPARATE. */
+ * OWNER gives every problem to one workgroup of 8 waves that runs all stages of the
+ * step - or, in finch_loop, of all steps - back to back (bf16: matrix instructions;
+ * fp32: the vector ALU, meant for small problems); batches it cannot run fail with
+ * FINCH_ERR_UNSUPPORTED.  AUTO (default) takes OWNER for bf16 when the batch has enough
+ * problems to fill the chip's compute units in whole rounds, for fp32 when no problem
+ * has more than 4096 candidates or 64 prompt rows, else SEPARATE. */
 typedef enum {
   FINCH_OPT_STEP_PATH = 1,
   /* tuning: target number of keys one workgroup of the two-pass bf16 scoring

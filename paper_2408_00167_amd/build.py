@@ -13,7 +13,7 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 LIB_PATH = os.path.join(PKG_DIR, "libfinch.so")
 
-SOURCES = ["api.hip", "score_bf16.hip", "owner_bf16.hip", "owner_doc_bf16.hip", "score_f32.hip", "select.hip", "reposition.hip", "prompt_lse.hip",
+SOURCES = ["api.hip", "score_bf16.hip", "owner_bf16.hip", "owner_doc_bf16.hip", "owner_f32.hip", "score_f32.hip", "select.hip", "reposition.hip", "prompt_lse.hip",
            "gather.hip"]
 
 HIPCC_FLAGS = [

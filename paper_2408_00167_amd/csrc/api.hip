@@ -138,6 +138,10 @@ finch_status make_plan(const finch_ctx* ctx, const finch_problem* hd, int32_t n_
     pl.own_lds = finch::owner_lds_bytes(ctx->cfg.head_dim, orc);
     pl.own_ok = pl.own_lds <= ctx->max_lds;
   }
+  if (ctx->cfg.dtype == FINCH_F32 && n_max > 0) {
+    pl.own_lds = finch::owner_f32_lds_bytes(ctx->cfg.head_dim);
+    pl.own_ok = pl.own_lds <= ctx->max_lds;
+  }
   size_t off = 256;  // the first word of the workspace is the status word of the launches (finch_workspace_status)
   pl.off_stats = off;
   const size_t na = static_cast<size_t>(n_alloc);
@@ -321,6 +325,9 @@ bool owner_wanted(const finch_ctx* ctx, const Plan& pl, int32_t n) {
   if (ctx->step_path == FINCH_PATH_OWNER) return true;
   if (pl.has_doc) return ctx->step_path == FINCH_PATH_AUTO;  // the only kernels with those rows
   if (ctx->step_path != FINCH_PATH_AUTO) return false;
+  // fp32 (vector ALU): one workgroup per problem saves launches while problems are small;
+  // large ones are better spread over the chip by the kernels per stage
+  if (ctx->cfg.dtype == FINCH_F32) return pl.n_max <= 4096 && pl.rows_max <= 64;
   const int64_t cu = ctx->n_cu > 0 ? ctx->n_cu : 256;
   const int64_t rounds = (n + cu - 1) / cu;
   return static_cast<int64_t>(n) * 100 >= rounds * cu * 85;
@@ -335,8 +342,9 @@ finch_status run_owner(finch_ctx* ctx, LaunchParams p, const Plan& pl, int stage
   }
   {
     ProfScope ps(ctx, FINCH_KERNEL_OWNER, s);
-    e = pl.has_doc ? finch::launch_owner_doc_bf16(ctx->cfg.head_dim, p, stages, s)
-                   : finch::launch_owner_bf16(ctx->cfg.head_dim, p, stages, s);
+    if (ctx->cfg.dtype == FINCH_F32) e = finch::launch_owner_f32(ctx->cfg.head_dim, p, stages, s);
+    else e = pl.has_doc ? finch::launch_owner_doc_bf16(ctx->cfg.head_dim, p, stages, s)
+                        : finch::launch_owner_bf16(ctx->cfg.head_dim, p, stages, s);
   }
   return e == hipSuccess ? FINCH_OK : hip_fail(ctx, e);
 }
@@ -593,6 +601,7 @@ finch_status finch_create(const finch_config* cfg, finch_ctx** out) {
   }
   if (e == hipSuccess && cfg->dtype == FINCH_BF16) e = finch::set_max_lds_owner(ctx->max_lds);
   if (e == hipSuccess && cfg->dtype == FINCH_BF16) e = finch::set_max_lds_owner_doc(ctx->max_lds);
+  if (e == hipSuccess && cfg->dtype == FINCH_F32) e = finch::set_max_lds_owner_f32(ctx->max_lds);
   // the re-positioning kernel also has a little static LDS
   if (e == hipSuccess) e = finch::set_max_lds_reposition(ctx->max_lds - 1024);
   if (e != hipSuccess) {
@@ -857,9 +866,12 @@ finch_status finch_loop(finch_ctx* ctx, const finch_problem* host_desc, const fi
     }
     {
       ProfScope ps(ctx, FINCH_KERNEL_OWNER, s);
-      e = pl.has_doc
-              ? finch::launch_owner_loop_doc_bf16(ctx->cfg.head_dim, p, dev_step_first, n_steps, n_slots, s)
-              : finch::launch_owner_loop_bf16(ctx->cfg.head_dim, p, dev_step_first, n_steps, n_slots, s);
+      if (ctx->cfg.dtype == FINCH_F32)
+        e = finch::launch_owner_loop_f32(ctx->cfg.head_dim, p, dev_step_first, n_steps, n_slots, s);
+      else
+        e = pl.has_doc
+                ? finch::launch_owner_loop_doc_bf16(ctx->cfg.head_dim, p, dev_step_first, n_steps, n_slots, s)
+                : finch::launch_owner_loop_bf16(ctx->cfg.head_dim, p, dev_step_first, n_steps, n_slots, s);
     }
     return e == hipSuccess ? FINCH_OK : hip_fail(ctx, e);
   }

@@ -84,6 +84,12 @@ hipError_t launch_owner_bf16(int head_dim, const LaunchParams& p, int stages, hi
 hipError_t launch_owner_loop_bf16(int head_dim, const LaunchParams& p, const int* step_first,
                                   int n_steps, int n_slots, hipStream_t s);
 hipError_t set_max_lds_owner(size_t bytes);
+// one workgroup per problem for fp32 inputs (prompt rows and rows of the chunk's own tokens)
+size_t owner_f32_lds_bytes(int head_dim);
+hipError_t launch_owner_f32(int head_dim, const LaunchParams& p, int stages, hipStream_t s);
+hipError_t launch_owner_loop_f32(int head_dim, const LaunchParams& p, const int* step_first, int n_steps,
+                                 int n_slots, hipStream_t s);
+hipError_t set_max_lds_owner_f32(size_t bytes);
 hipError_t launch_zero_words(int32_t* words, int n, int32_t* one_more, hipStream_t s);
 // the same with rows of the chunk's own tokens (desc.q_doc)
 hipError_t launch_owner_doc_bf16(int head_dim, const LaunchParams& p, int stages, hipStream_t s);

@@ -82,12 +82,12 @@ __device__ __forceinline__ void own_gather(const finch_problem& pb, int N, int r
 // at place p of the sorted records; the key is turned by p - idx[t] positions while it
 // is copied (not at all with pairing FINCH_ROPE_OFF).  A thread owns two pieces of a
 // row, d/2 channels apart, i.e. both partners of its channel pairs.
-template <int SEGS, int NT = kOwnThreads>
+template <int SEGS, int NT = kOwnThreads, int E = 8>
 __device__ __forceinline__ void own_gather_rot(const finch_problem& pb, int N, int r, const int* lidx,
                                                const FINCH_GLOBAL int* gidx, bool identity, int pairing,
                                                double log2_base, int tid,
                                                const unsigned long long* ranked = nullptr) {
-  constexpr int kHalf = SEGS / 2, E = 8;
+  constexpr int kHalf = SEGS / 2;
   const FINCH_GLOBAL u32x4* kc = as_global<u32x4>(pb.k_cache);
   const FINCH_GLOBAL u32x4* kk = as_global<u32x4>(pb.k_chunk);
   const FINCH_GLOBAL u32x4* vc = as_global<u32x4>(pb.v_cache);
@@ -164,6 +164,94 @@ __device__ __forceinline__ void own_rank_kept(unsigned long long* ranked, int r,
       }
       __syncthreads();
     }
+  }
+}
+
+// The rest of a step once this workgroup's scores are in memory (and a barrier has been
+// passed since): top-r (Method: t = top-r(A_agg, r); with `layered` on the sum over the
+// layer's heads) and compaction (Method: Managing the Cache) of rows of SEGS 16-byte
+// pieces with E elements each.  `sel` is LDS scratch of sel_bytes (>= sizeof(SelLds) +
+// kOwnerSelectBytes); `dst` the scores of this problem.
+template <int SEGS, int E, bool ROT>
+__device__ __forceinline__ void own_finish_step(const LaunchParams& prm, const finch_problem& pb, int slot, int N,
+                                                FINCH_GLOBAL float* dst, char* sel, size_t sel_bytes,
+                                                const finch_problem* step_probs, int epoch, bool layered,
+                                                int* sync_words, int tid) {
+  const int lane = tid & 63, wave = tid >> 6;
+  const int L = prm.layer_group;
+  // ---- top-r on the scores this workgroup has just written
+  const int r = min(pb.r, N);
+  if (r <= 0) return;
+  FINCH_GLOBAL int* gidx = as_global_mut<int>(pb.idx);
+  const bool identity = r >= N;
+  SelLds* fl = reinterpret_cast<SelLds*>(sel);
+  int* lidx = nullptr;
+  if (identity) {
+    for (int i = tid; i < N; i += kOwnThreads) gidx[i] = i;
+  } else {
+    size_t used = sizeof(SelLds);
+    if (used + static_cast<size_t>(r) * 4 <= sel_bytes) {
+      lidx = reinterpret_cast<int*>(sel + used);
+      used += static_cast<size_t>(r) * 4;
+    }
+    if (layered) {
+      // this workgroup's scores are out (stored past the caches, and every thread has waited
+      // for its own stores at the barrier after pass 2); wait until all L workgroups of the
+      // run say the same
+      const int run = slot / L;
+      if (tid == 0) {
+        __hip_atomic_fetch_add(sync_words, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const long long t0 = wall_clock64();
+        while (__hip_atomic_load(sync_words, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < L * (epoch + 1)) {
+          __builtin_amdgcn_s_sleep(8);
+          if (wall_clock64() - t0 > prm.spin_ticks) {
+            atomicOr(prm.layer_err, 1);
+            break;
+          }
+        }
+      }
+      if (tid < L) {
+        const finch_problem pg = step_probs[run * L + tid];
+        fl->layer_src[tid] = pg.scores ? pg.scores
+                                       : prm.ws_scores + static_cast<size_t>(run * L + tid) * prm.score_stride;
+      }
+      __syncthreads();
+    }
+    const LayerScores layer_sum = {fl->layer_src, L};
+    const OneScoreVector own = {dst};
+    if (N <= kOwnThreads * kSelRegKeys) {
+      if (layered) select_regs<kOwnThreads>(layer_sum, N, r, gidx, lidx, fl, tid, lane, wave);
+      else select_regs<kOwnThreads>(own, N, r, gidx, lidx, fl, tid, lane, wave);
+    } else {
+      unsigned* lkeys = nullptr;
+      if (used + static_cast<size_t>(N) * 4 <= sel_bytes) {
+        lkeys = reinterpret_cast<unsigned*>(sel + used);
+        for (int i = tid; i < N; i += kOwnThreads) lkeys[i] = order_key(layered ? layer_sum(i) : own(i));
+      }
+      __syncthreads();
+      if (layered) select_generic<kOwnThreads>(lkeys, layer_sum, N, r, gidx, lidx, fl, tid, lane, wave);
+      else select_generic<kOwnThreads>(lkeys, own, N, r, gidx, lidx, fl, tid, lane, wave);
+    }
+    __syncthreads();  // idx (LDS and memory) complete
+    // (the other workgroups' scores have been read for the last time)
+    if (layered && tid == 0) __hip_atomic_fetch_add(sync_words + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+
+  // ---- compaction
+  if (ROT) {
+    // slots by relevance (Method: Managing the Cache, the worked example): the rank of a kept
+    // row's score among the kept ones, highest first, equal scores by index.  The host
+    // sends such batches here only if the indices and the records of all kept rows fit
+    // behind the selection scratch.
+    unsigned long long* ranked = nullptr;
+    if (prm.rank_order) {
+      __syncthreads();  // (the identity case has not been through a barrier since the scores)
+      ranked = reinterpret_cast<unsigned long long*>(sel + sizeof(SelLds) + ((static_cast<size_t>(r) * 4 + 7) & ~size_t{7}));
+      own_rank_kept(ranked, r, dst, lidx, identity, tid);
+    }
+    own_gather_rot<SEGS, kOwnThreads, E>(pb, N, r, lidx, gidx, identity, prm.rope_pairing, prm.rope_log2_base, tid, ranked);
+  } else {
+    own_gather<SEGS>(pb, N, r, lidx, gidx, identity, tid);
   }
 }
 
@@ -456,83 +544,11 @@ __device__ __forceinline__ bool own_step_body(const LaunchParams& prm, const fin
   staged_rows = Rp;
   if (!stages) return false;
 
-  // ---- top-r on the scores this workgroup has just written
-  const int r = min(pb.r, N);
-  if (r <= 0) return false;
-  FINCH_GLOBAL int* gidx = as_global_mut<int>(pb.idx);
-  const bool identity = r >= N;
-  // selection scratch: behind the staged prompt rows (pass-1 statistics are dead)
-  char* sel = smem + RC * kStride;
-  const size_t sel_bytes = prm.lds_bytes - static_cast<size_t>(RC) * kStride;
-  SelLds* fl = reinterpret_cast<SelLds*>(sel);
-  int* lidx = nullptr;
-  if (identity) {
-    for (int i = tid; i < N; i += kOwnThreads) gidx[i] = i;
-  } else {
-    size_t used = sizeof(SelLds);
-    if (used + static_cast<size_t>(r) * 4 <= sel_bytes) {
-      lidx = reinterpret_cast<int*>(sel + used);
-      used += static_cast<size_t>(r) * 4;
-    }
-    if (layered) {
-      // this workgroup's scores are out (stored past the caches, and every thread has waited
-      // for its own stores at the barrier after pass 2); wait until all L workgroups of the
-      // run say the same
-      const int run = slot / L;
-      if (tid == 0) {
-        __hip_atomic_fetch_add(sync_words, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const long long t0 = wall_clock64();
-        while (__hip_atomic_load(sync_words, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < L * (epoch + 1)) {
-          __builtin_amdgcn_s_sleep(8);
-          if (wall_clock64() - t0 > prm.spin_ticks) {
-            atomicOr(prm.layer_err, 1);
-            break;
-          }
-        }
-      }
-      if (tid < L) {
-        const finch_problem pg = step_probs[run * L + tid];
-        fl->layer_src[tid] = pg.scores ? pg.scores
-                                       : prm.ws_scores + static_cast<size_t>(run * L + tid) * prm.score_stride;
-      }
-      __syncthreads();
-    }
-    const LayerScores layer_sum = {fl->layer_src, L};
-    const OneScoreVector own = {dst};
-    if (N <= kOwnThreads * kSelRegKeys) {
-      if (layered) select_regs<kOwnThreads>(layer_sum, N, r, gidx, lidx, fl, tid, lane, wave);
-      else select_regs<kOwnThreads>(own, N, r, gidx, lidx, fl, tid, lane, wave);
-    } else {
-      unsigned* lkeys = nullptr;
-      if (used + static_cast<size_t>(N) * 4 <= sel_bytes) {
-        lkeys = reinterpret_cast<unsigned*>(sel + used);
-        for (int i = tid; i < N; i += kOwnThreads) lkeys[i] = order_key(layered ? layer_sum(i) : own(i));
-      }
-      __syncthreads();
-      if (layered) select_generic<kOwnThreads>(lkeys, layer_sum, N, r, gidx, lidx, fl, tid, lane, wave);
-      else select_generic<kOwnThreads>(lkeys, own, N, r, gidx, lidx, fl, tid, lane, wave);
-    }
-    __syncthreads();  // idx (LDS and memory) complete
-    // (the other workgroups' scores have been read for the last time)
-    if (layered && tid == 0) __hip_atomic_fetch_add(sync_words + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
-
-  // ---- compaction
-  if (ROT) {
-    // slots by relevance (Method: Managing the Cache, the worked example): the rank of a kept
-    // row's score among the kept ones, highest first, equal scores by index.  The host
-    // sends such batches here only if the indices and the records of all kept rows fit
-    // behind the selection scratch.
-    unsigned long long* ranked = nullptr;
-    if (prm.rank_order) {
-      __syncthreads();  // (the identity case has not been through a barrier since the scores)
-      ranked = reinterpret_cast<unsigned long long*>(sel + sizeof(SelLds) + ((static_cast<size_t>(r) * 4 + 7) & ~size_t{7}));
-      own_rank_kept(ranked, r, dst, lidx, identity, tid);
-    }
-    own_gather_rot<D / 8>(pb, N, r, lidx, gidx, identity, prm.rope_pairing, prm.rope_log2_base, tid, ranked);
-  } else {
-    own_gather<D / 8>(pb, N, r, lidx, gidx, identity, tid);
-  }
+  // ---- top-r and compaction; selection scratch behind the staged prompt rows (the pass-1
+  // statistics are dead)
+  own_finish_step<D / 8, 8, ROT>(prm, pb, slot, N, dst, smem + RC * kStride,
+                                 prm.lds_bytes - static_cast<size_t>(RC) * kStride, step_probs, epoch, layered,
+                                 sync_words, tid);
   return layered;
 }
 

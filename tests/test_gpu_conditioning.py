@@ -29,11 +29,13 @@ def say(msg):
     print(msg, flush=True)
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
 @pytest.mark.parametrize("d,group", [(128, 4), (64, 1), (128, 1), (64, 3)])
-def test_document_rows_with_causal_mask(d, group):
-    say(f"conditioning d={d} G={group}")
-    fin = F.Finch(F.FINCH_BF16, d, group)
-    batch, ts = H.single_step_case(fin, SPECS, torch.bfloat16, d, group, seed=1100 + d + group)
+def test_document_rows_with_causal_mask(d, group, dtype):
+    say(f"conditioning d={d} G={group} {dtype}")
+    fin = F.Finch(H.finch_dtype(torch.empty(0, dtype=dtype)), d, group)
+    specs = SPECS if dtype == torch.bfloat16 else [dict(sp, m=min(sp["m"], 300), c=min(sp["c"], 200)) for sp in SPECS]
+    batch, ts = H.single_step_case(fin, specs, dtype, d, group, seed=1100 + d + group)
     with_keys = F.Batch([t for t in batch_descs(ts) if t.get("k_que") is not None])
     fin.prompt_lse(with_keys)
     fin.step(batch)
@@ -134,9 +136,14 @@ def test_paths_without_those_rows_refuse():
     fin.step(batch)
     H.validate_single_step(ts, "after the refused calls")
     fin.close()
+    # fp32: the same rule (rows of the chunk's own tokens only with one workgroup per problem)
     f32 = F.Finch(F.FINCH_F32, 64, 1)
     batch, ts = H.single_step_case(f32, sp, torch.float32, 64, 1, seed=4)
+    f32.set_step_path(F.FINCH_PATH_SEPARATE)
     with pytest.raises(F.FinchError) as e:
         f32.step(batch)
     assert e.value.status == F.FINCH_ERR_UNSUPPORTED
+    f32.set_step_path(F.FINCH_PATH_AUTO)
+    f32.step(batch)
+    H.validate_single_step(ts, "fp32 document rows")
     f32.close()

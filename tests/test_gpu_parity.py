@@ -87,16 +87,26 @@ def test_both_step_paths(d, group, path):
     fin.close()
 
 
-def test_forced_owner_path_rejects_fp32():
-    fin = F.Finch(F.FINCH_F32, 64, 1)
+FP32_SPECS = [dict(n_que=16, c=48, m=256, r=64), dict(n_que=4, c=0, m=64, r=8), dict(n_que=1, c=7, m=0, r=3),
+              dict(n_que=33, c=100, m=1300, r=333), dict(n_que=5, c=10, m=20, r=40), dict(n_que=9, c=0, m=700, r=0)]
+
+
+@pytest.mark.parametrize("d,group", [(64, 1), (128, 2), (64, 5)])
+def test_fp32_one_workgroup_per_problem(d, group):
+    """fp32 inputs through the one-workgroup-per-problem kernels (vector ALU): the same
+    results as the kernels per stage, to the oracle's tolerance."""
+    say(f"fp32 owner d={d} G={group}")
+    fin = F.Finch(F.FINCH_F32, d, group)
     fin.set_step_path(F.FINCH_PATH_OWNER)
-    batch, ts = H.single_step_case(fin, [dict(n_que=4, c=0, m=64, r=8)], torch.float32, 64, 1, seed=1)
-    with pytest.raises(F.FinchError) as e:
-        fin.step(batch)
-    assert e.value.status == F.FINCH_ERR_UNSUPPORTED
-    fin.set_step_path(F.FINCH_PATH_AUTO)
+    batch, ts = H.single_step_case(fin, FP32_SPECS, torch.float32, d, group, seed=70 + d)
     fin.step(batch)
-    H.validate_single_step(ts, "fp32 after the rejected call")
+    st = H.validate_single_step(ts, f"fp32 owner d={d} G={group}")
+    say(f"  worst score rel err {st['worst_rel']:.2e}, near-tie swaps {st['swaps']}")
+    assert _which_scoring_kernels(fin, batch) == {"owner"}
+    fin.set_step_path(F.FINCH_PATH_SEPARATE)
+    b2, t2 = H.single_step_case(fin, FP32_SPECS, torch.float32, d, group, seed=70 + d)
+    fin.step(b2)
+    H.validate_single_step(t2, f"fp32 per stage d={d} G={group}")
     fin.close()
 
 
@@ -283,9 +293,22 @@ def test_c1_full_workload():
     probs = [H.make_gpu_problem(w, b, l, g) for b, l, g in W.problems_of(w)]
     loop = ChunkLoop(fin, probs, w.chunk, history=True)
     assert [r for r in loop.rs[0]] == [16, 32, 48, 64]
+    F.finch_profile(fin.ctx, True)
     loop.run()
+    torch.cuda.synchronize()
+    prof = F.finch_profile_read(fin.ctx)
+    F.finch_profile(fin.ctx, False)
+    # the whole loop of the batch is one launch
+    assert {k: v["launches"] for k, v in prof.items() if v["launches"]} == {"owner": 1}, prof
     st = H.validate_chunk_loop(loop, range(len(probs)), "C1")
     say(f"  C1: {st}")
+    # ... and one kernel per stage, step by step, gives the same selection
+    fin.set_step_path(F.FINCH_PATH_SEPARATE)
+    loop2 = ChunkLoop(fin, probs, w.chunk, history=True)
+    loop2.run()
+    H.validate_chunk_loop(loop2, range(len(probs)), "C1 per stage")
+    assert torch.equal(loop.idx, loop2.idx)
+    fin.set_step_path(F.FINCH_PATH_AUTO)
     # the planted keys are what the method is supposed to keep
     for p, pb in enumerate(probs):
         Kt, _ = loop.final_cache(p)
