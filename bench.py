@@ -150,7 +150,15 @@ def main() -> int:
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain elementwise copy of 1 GiB (read 1 GiB, write 1 GiB) three "
                          "times, so that a counter run of this command holds a kernel of known traffic")
+    ap.add_argument("--phases", action="store_true",
+                    help="load the measurement build with phase timers (python -m paper_2408_00167_amd.build "
+                         "--phase-timers) and add the time per phase of a step of the one-workgroup-per-"
+                         "problem kernels; the timed loop then runs the instrumented kernels")
     args = ap.parse_args()
+    if args.phases:
+        # (before the binding is imported: it reads the library's path once)
+        os.environ["FINCH_LIBRARY"] = os.path.join(os.path.dirname(os.path.abspath(__file__)),
+                                                   "paper_2408_00167_amd", "libfinch_phases.so")
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (problems are independent; there is no "
               "multi-GPU path to measure). Re-run with --gpus 1.", file=sys.stderr)
@@ -201,6 +209,14 @@ def main() -> int:
     for _ in range(args.warmup):
         loop.run(per_step=args.per_step)
     torch.cuda.synchronize()
+    phase_fn = None
+    if args.phases:
+        import ctypes
+        phase_fn = F.load_library().finch_debug_phases
+        phase_fn.argtypes = [ctypes.POINTER(ctypes.c_ulonglong), ctypes.c_int]
+        phase_fn.restype = ctypes.c_int
+        phase_buf = (ctypes.c_ulonglong * 8)()
+        assert phase_fn(phase_buf, 1) == 0
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     ev0.record()
@@ -211,6 +227,16 @@ def main() -> int:
     wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
     ev_ms = ev0.elapsed_time(ev1) / args.steps
     ms = wall_ms
+    phases = None
+    if phase_fn is not None:
+        # thread 0 of each workgroup has added up its 10 ns ticks per phase over the timed loops
+        assert phase_fn(phase_buf, 0) == 0
+        names = ["stage_prompt_rows", "pass1_wave0", "pass1_barrier_wait", "merge_row_statistics", "pass2_wave0",
+                 "pass2_barrier_wait", "top_r", "compaction"]
+        per = args.steps * len(probs) * loop.n_steps
+        phases = {n: phase_buf[i] * 0.01 / per for i, n in enumerate(names)}
+        phases["sum"] = sum(phases.values())
+        phases["unit"] = "us per chunk step, mean over workgroups"
 
     if args.copy_calibration:
         src = torch.ones(COPY_CALIBRATION_BYTES // 4, dtype=torch.float32, device=dev)
@@ -291,6 +317,8 @@ def main() -> int:
         "matrix_pipe": matrix_pipe,
         "setup_s": t_gen,
     }
+    if phases is not None:
+        out["phases"] = phases
     if not args.no_cpu_baseline:
         order = list(W.problems_of(w))
 

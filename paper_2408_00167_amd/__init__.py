@@ -14,7 +14,9 @@ import os
 from typing import Dict, List, Optional, Sequence
 
 _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG_DIR, "libfinch.so")
+# FINCH_LIBRARY names another build of the same sources to load instead (the measurement build
+# with phase timers, libfinch_phases.so); it must exist - there is no fallback.
+LIB_PATH = os.environ.get("FINCH_LIBRARY") or os.path.join(_PKG_DIR, "libfinch.so")
 
 FINCH_OK = 0
 FINCH_ERR_INVALID_ARG = -1

@@ -1,6 +1,11 @@
 """Builds libfinch.so (HIP kernels + C ABI) for gfx950, in-tree.
 
 Usage: python -m paper_2408_00167_amd.build
+       python -m paper_2408_00167_amd.build --phase-timers
+The second form writes libfinch_phases.so beside it: the same sources with
+-DFINCH_PHASE_TIMERS, i.e. with clock reads between the phases of a step in the
+one-workgroup-per-problem kernels (a measurement build: `bench.py --phases` loads it;
+nothing else does).
 """
 from __future__ import annotations
 
@@ -12,6 +17,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 LIB_PATH = os.path.join(PKG_DIR, "libfinch.so")
+PHASES_LIB_PATH = os.path.join(PKG_DIR, "libfinch_phases.so")
 
 SOURCES = ["api.hip", "score_bf16.hip", "owner_bf16.hip", "owner_doc_bf16.hip", "owner_f32.hip", "score_f32.hip", "select.hip", "reposition.hip", "prompt_lse.hip",
            "gather.hip"]
@@ -41,10 +47,14 @@ def _run(cmd, verbose: bool) -> None:
         raise RuntimeError(f"hipcc failed ({proc.returncode}): {' '.join(cmd)}\n{out}")
 
 
-def build_library(verbose: bool = True, extra_flags=(), jobs: int = 0) -> str:
-    """Compiles every source to an object (in parallel), then links libfinch.so."""
+def build_library(verbose: bool = True, extra_flags=(), jobs: int = 0, phase_timers: bool = False) -> str:
+    """Compiles every source to an object (in parallel), then links libfinch.so
+    (libfinch_phases.so with the phase timers compiled in)."""
     from concurrent.futures import ThreadPoolExecutor
-    obj_dir = os.path.join(PKG_DIR, "_build")
+    obj_dir = os.path.join(PKG_DIR, "_build_phases" if phase_timers else "_build")
+    lib_path = PHASES_LIB_PATH if phase_timers else LIB_PATH
+    if phase_timers:
+        extra_flags = (*extra_flags, "-DFINCH_PHASE_TIMERS")
     os.makedirs(obj_dir, exist_ok=True)
     hipcc = hipcc_path()
     jobs = jobs or min(len(SOURCES), max(1, (os.cpu_count() or 2) - 1), 8)
@@ -60,14 +70,13 @@ def build_library(verbose: bool = True, extra_flags=(), jobs: int = 0) -> str:
 
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         list(pool.map(compile_one, zip(SOURCES, objs)))
-    link = [hipcc, "--offload-arch=gfx950", "-fno-gpu-rdc", "-shared", "-fPIC", *objs, "-o", LIB_PATH]
+    link = [hipcc, "--offload-arch=gfx950", "-fno-gpu-rdc", "-shared", "-fPIC", *objs, "-o", lib_path]
     if verbose:
         print(" ".join(link), flush=True)
     _run(link, verbose)
-    return LIB_PATH
+    return lib_path
 
 
 if __name__ == "__main__":
-    build_library()
-    print("built", LIB_PATH)
+    print("built", build_library(phase_timers="--phase-timers" in sys.argv[1:]))
     sys.exit(0)

@@ -27,3 +27,15 @@ hipError_t launch_owner_loop_bf16(int head_dim, const LaunchParams& p, const int
 hipError_t set_max_lds_owner(size_t bytes) { return set_max_lds_owner_impl<false>(bytes); }
 
 }  // namespace finch
+
+#ifdef FINCH_PHASE_TIMERS
+// Phase-timer build only: the totals of the kernels of this file (prompt rows only) on the
+// current device, 8 words of wall-clock ticks (10 ns); reset != 0 clears them instead.
+extern "C" int finch_debug_phases(unsigned long long* out, int reset) {
+  if (reset) {
+    const unsigned long long zero[8] = {0};
+    return static_cast<int>(hipMemcpyToSymbol(HIP_SYMBOL(finch::finch_phase_ticks), zero, sizeof(zero)));
+  }
+  return static_cast<int>(hipMemcpyFromSymbol(out, HIP_SYMBOL(finch::finch_phase_ticks), sizeof(unsigned long long) * 8));
+}
+#endif

@@ -30,6 +30,28 @@ namespace finch {
 
 namespace {
 
+// Phase timers, compiled in only with -DFINCH_PHASE_TIMERS (the build script's --phase-timers
+// writes that variant to a library of its own; the normal library has none of this).  Thread 0
+// of every workgroup adds the ticks of the 100 MHz wall clock it spent between two marks to
+// the phase's total: 0 staging of the prompt rows, 1 pass 1 of wave 0, 2 wave 0's wait at the
+// barrier after pass 1, 3 merge of the row statistics, 4 pass 2 of wave 0, 5 its wait at the
+// barrier after pass 2, 6 top-r, 7 compaction.  Each translation unit has its own totals.
+#ifdef FINCH_PHASE_TIMERS
+static __device__ unsigned long long finch_phase_ticks[8];
+#define FINCH_PHASE_BEGIN() unsigned long long phase_last_ = wall_clock64()
+#define FINCH_PHASE(i)                                        \
+  do {                                                        \
+    if (threadIdx.x == 0) {                                   \
+      const unsigned long long now_ = wall_clock64();         \
+      atomicAdd(&finch_phase_ticks[i], now_ - phase_last_);   \
+      phase_last_ = now_;                                     \
+    }                                                         \
+  } while (0)
+#else
+#define FINCH_PHASE_BEGIN() do { } while (0)
+#define FINCH_PHASE(i) do { } while (0)
+#endif
+
 constexpr int kOwnThreads = 512;
 constexpr int kOwnWaves = kOwnThreads / 64;
 
@@ -138,6 +160,9 @@ __device__ __forceinline__ void own_gather_rot(const finch_problem& pb, int N, i
 // over the next power of two (padding records are zero and end up last), so that place
 // p holds the row with the p-th highest score, equal scores in index order.  `ranked`
 // needs 8 * 2^ceil(log2 r) bytes of LDS.  Whole workgroup; ends with a barrier.
+// Each wave owns one eighth of the array (all of it goes to wave 0 below 256 records):
+// the stages whose partners lie inside a wave's part - most of them - need no workgroup
+// barrier, the LDS serves a wave's reads and writes in the order it issued them.
 __device__ __forceinline__ void own_rank_kept(unsigned long long* ranked, int r, const FINCH_GLOBAL float* scores,
                                               const int* lidx, bool identity, int tid) {
   int npad = 2;
@@ -149,22 +174,38 @@ __device__ __forceinline__ void own_rank_kept(unsigned long long* ranked, int r,
     ranked[u] = rec;
   }
   __syncthreads();
+  const int lane = tid & 63, wave = tid >> 6;
+  const int part = npad >= 256 ? npad / kOwnWaves : npad;  // records per wave
+  // pair number q of the stage with partner distance j: i has bit j clear, its partner is i + j
+  auto exchange = [&](int q, int j, int k) {
+    const int i = ((q & ~(j - 1)) << 1) | (q & (j - 1));
+    const unsigned long long a = ranked[i], b = ranked[i + j];
+    const bool descending = (i & k) == 0;
+    if (descending ? a < b : a > b) {
+      ranked[i] = b;
+      ranked[i + j] = a;
+    }
+  };
+  bool across = false;  // the stage before this one exchanged records between the waves' parts
   for (int k = 2; k <= npad; k <<= 1) {
     for (int j = k >> 1; j > 0; j >>= 1) {
-      for (int i = tid; i < npad; i += kOwnThreads) {
-        const int x = i ^ j;
-        if (x > i) {
-          const unsigned long long a = ranked[i], b = ranked[x];
-          const bool descending = (i & k) == 0;
-          if (descending ? a < b : a > b) {
-            ranked[i] = b;
-            ranked[x] = a;
-          }
+      if (j >= part) {
+        __syncthreads();
+        for (int q = tid; q < (npad >> 1); q += kOwnThreads) exchange(q, j, k);
+        across = true;
+      } else {
+        if (across) __syncthreads();
+        across = false;
+        if (wave * part < npad) {
+          const int q0 = wave * (part >> 1);
+          for (int q = lane; q < (part >> 1); q += 64) exchange(q0 + q, j, k);
         }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
       }
-      __syncthreads();
     }
   }
+  __syncthreads();
 }
 
 // The rest of a step once this workgroup's scores are in memory (and a barrier has been
@@ -179,6 +220,7 @@ __device__ __forceinline__ void own_finish_step(const LaunchParams& prm, const f
                                                 int* sync_words, int tid) {
   const int lane = tid & 63, wave = tid >> 6;
   const int L = prm.layer_group;
+  FINCH_PHASE_BEGIN();
   // ---- top-r on the scores this workgroup has just written
   const int r = min(pb.r, N);
   if (r <= 0) return;
@@ -236,6 +278,7 @@ __device__ __forceinline__ void own_finish_step(const LaunchParams& prm, const f
     // (the other workgroups' scores have been read for the last time)
     if (layered && tid == 0) __hip_atomic_fetch_add(sync_words + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
+  FINCH_PHASE(6);
 
   // ---- compaction
   if (ROT) {
@@ -253,6 +296,7 @@ __device__ __forceinline__ void own_finish_step(const LaunchParams& prm, const f
   } else {
     own_gather<SEGS>(pb, N, r, lidx, gidx, identity, tid);
   }
+  FINCH_PHASE(7);
 }
 
 // One step of one problem by the whole workgroup.  QBT = row blocks (of 32 prompt
@@ -277,6 +321,7 @@ __device__ __forceinline__ bool own_step_body(const LaunchParams& prm, const fin
                                               int epoch = 0) {
   const int N = pb.c + pb.m;
   if (N == 0) return false;
+  FINCH_PHASE_BEGIN();
   const int Rp = (DOC && !pb.q) ? 0 : prm.group * pb.n_que;  // prompt rows
   // (the thread index goes through an empty asm: in the whole-loop kernel the compiler
   // would otherwise compute everything that depends only on it once for all steps and
@@ -352,6 +397,7 @@ __device__ __forceinline__ bool own_step_body(const LaunchParams& prm, const fin
       __syncthreads();
     }
     staged_q = nullptr;
+    FINCH_PHASE(0);
 
     // ---- pass 1: running (reference, sum exp2) per prompt row, fixed block assignment
     {
@@ -451,12 +497,14 @@ __device__ __forceinline__ bool own_step_body(const LaunchParams& prm, const fin
       }
     }
 
+    FINCH_PHASE(1);
     // ---- pass 2 walks the keys from the end (what pass 1 read last is what the
     // caches most likely still hold); its first block is requested before the merge
     b = nbc - 1 - wave;
     if (b >= 0) load_k_block<D>(ks, N, b << 5, lane, ka);
     if (tid == 0) *sh_next = kOwnWaves;
     __syncthreads();
+    FINCH_PHASE(2);
     for (int i = tid; i < rows; i += kOwnThreads) {
       float l = kInf;  // padding rows add exp2(-inf) = 0
       if (row0 + i < R) {
@@ -477,6 +525,7 @@ __device__ __forceinline__ bool own_step_body(const LaunchParams& prm, const fin
       lds_lse[i] = l;
     }
     __syncthreads();
+    FINCH_PHASE(3);
     {
       auto process = [&](const bf16x8(&kf)[D / 16], int blk) {
         const int kbase = blk << 5;
@@ -537,7 +586,9 @@ __device__ __forceinline__ bool own_step_body(const LaunchParams& prm, const fin
         }
       }
     }
+    FINCH_PHASE(4);
     __syncthreads();  // scores of this row chunk are out; LDS may be restaged
+    FINCH_PHASE(5);
   }
   // what the prompt-row region of LDS holds now (selection scratch lies behind it)
   staged_q = (n_chunks == 1) ? pb.q : nullptr;
