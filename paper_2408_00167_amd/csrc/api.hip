@@ -309,10 +309,10 @@ bool repositioning(const finch_ctx* ctx) {
 bool owner_wanted(const finch_ctx* ctx, const Plan& pl, int32_t n) {
   if (!pl.own_ok || n <= 0) return false;
   // slots by score rank: the workgroup sorts its kept rows in LDS (their indices and one
-  // 64-bit record each, padded to a power of two, behind the selection scratch), and a
+  // 64-bit record each, padded to a power of two of at least 64, behind the selection scratch), and a
   // layer's heads would have to share the slots
   if (ctx->repos.order == FINCH_ORDER_RANK) {
-    size_t npad = 2;
+    size_t npad = 64;
     while (npad < static_cast<size_t>(pl.r_max)) npad <<= 1;
     if (static_cast<size_t>(pl.r_max) * 4 + 8 + npad * 8 > finch::kOwnerSelectBytes || ctx->layer_group > 1)
       return false;

@@ -157,55 +157,98 @@ __device__ __forceinline__ void own_gather_rot(const finch_problem& pb, int N, i
 
 // Kept rows by relevance: one 64-bit record per kept row t < r - order key of its score
 // in the upper half, ~t in the lower - sorted in descending order by a bitonic network
-// over the next power of two (padding records are zero and end up last), so that place
-// p holds the row with the p-th highest score, equal scores in index order.  `ranked`
-// needs 8 * 2^ceil(log2 r) bytes of LDS.  Whole workgroup; ends with a barrier.
-// Each wave owns one eighth of the array (all of it goes to wave 0 below 256 records):
-// the stages whose partners lie inside a wave's part - most of them - need no workgroup
-// barrier, the LDS serves a wave's reads and writes in the order it issued them.
+// over npad = max(64, next power of two) records (padding records are zero and end up
+// last), so that place p holds the row with the p-th highest score, equal scores in index
+// order.  `ranked` needs 8 * npad bytes of LDS.  Whole workgroup; ends with a barrier.
+// A wave owns a part of max(64, npad / 8) consecutive records and keeps them in registers,
+// record lane + 64 s of the part in slot s of the lane: partners less than 64 apart are
+// exchanged by lane shuffles, partners 64 or 128 apart sit in the same lane, and only the
+// stages whose partners lie in different parts go through LDS and workgroup barriers.
+constexpr int kRankSlots = 4;  // records per lane: parts of at most 256 records = 2048 kept rows
+__device__ __forceinline__ int own_rank_pad(int r) {
+  int npad = 64;
+  while (npad < r) npad <<= 1;
+  return npad;
+}
 __device__ __forceinline__ void own_rank_kept(unsigned long long* ranked, int r, const FINCH_GLOBAL float* scores,
                                               const int* lidx, bool identity, int tid) {
-  int npad = 2;
-  while (npad < r) npad <<= 1;
-  for (int u = tid; u < npad; u += kOwnThreads) {
-    unsigned long long rec = 0ull;
-    if (u < r)
-      rec = (static_cast<unsigned long long>(order_key(scores[identity ? u : lidx[u]])) << 32) | static_cast<unsigned>(~u);
-    ranked[u] = rec;
-  }
-  __syncthreads();
+  const int npad = own_rank_pad(r);
   const int lane = tid & 63, wave = tid >> 6;
-  const int part = npad >= 256 ? npad / kOwnWaves : npad;  // records per wave
-  // pair number q of the stage with partner distance j: i has bit j clear, its partner is i + j
-  auto exchange = [&](int q, int j, int k) {
-    const int i = ((q & ~(j - 1)) << 1) | (q & (j - 1));
-    const unsigned long long a = ranked[i], b = ranked[i + j];
-    const bool descending = (i & k) == 0;
-    if (descending ? a < b : a > b) {
-      ranked[i] = b;
-      ranked[i + j] = a;
-    }
+  const int part = max(64, npad / kOwnWaves);
+  const int slots = part >> 6;  // 1, 2 or 4
+  const bool active = wave * part < npad;
+  const int e0 = wave * part + lane;  // slot s holds record e0 + 64 s
+  unsigned long long rec[kRankSlots];
+#pragma unroll
+  for (int sl = 0; sl < kRankSlots; ++sl) {
+    rec[sl] = 0ull;
+    const int u = e0 + 64 * sl;
+    if (active && sl < slots && u < r)
+      rec[sl] = (static_cast<unsigned long long>(order_key(scores[identity ? u : lidx[u]])) << 32) | static_cast<unsigned>(~u);
+  }
+  // the record that stays at position e after the exchange with position e ^ j in the stage (k, j)
+  auto keep = [](unsigned long long mine, unsigned long long other, int e, int j, int k) {
+    const bool want_max = ((e & k) == 0) == ((e & j) == 0);
+    return want_max ? (mine > other ? mine : other) : (mine < other ? mine : other);
   };
-  bool across = false;  // the stage before this one exchanged records between the waves' parts
+  bool in_lds = false;  // the current order is in `ranked`, not in the registers
   for (int k = 2; k <= npad; k <<= 1) {
     for (int j = k >> 1; j > 0; j >>= 1) {
       if (j >= part) {
-        __syncthreads();
-        for (int q = tid; q < (npad >> 1); q += kOwnThreads) exchange(q, j, k);
-        across = true;
-      } else {
-        if (across) __syncthreads();
-        across = false;
-        if (wave * part < npad) {
-          const int q0 = wave * (part >> 1);
-          for (int q = lane; q < (part >> 1); q += 64) exchange(q0 + q, j, k);
+        if (!in_lds) {
+#pragma unroll
+          for (int sl = 0; sl < kRankSlots; ++sl)
+            if (active && sl < slots) ranked[e0 + 64 * sl] = rec[sl];
         }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
+        __syncthreads();
+        for (int q = tid; q < (npad >> 1); q += kOwnThreads) {
+          const int i = ((q & ~(j - 1)) << 1) | (q & (j - 1));
+          const unsigned long long a = ranked[i], b = ranked[i + j];
+          if (((i & k) == 0) ? a < b : a > b) {
+            ranked[i] = b;
+            ranked[i + j] = a;
+          }
+        }
+        in_lds = true;
+        continue;
+      }
+      if (in_lds) {
+        __syncthreads();
+#pragma unroll
+        for (int sl = 0; sl < kRankSlots; ++sl)
+          if (active && sl < slots) rec[sl] = ranked[e0 + 64 * sl];
+        in_lds = false;
+      }
+      if (j >= 64) {
+        // partner in the same lane, j / 64 slots away (1 or 2)
+        unsigned long long nxt[kRankSlots];
+#pragma unroll
+        for (int sl = 0; sl < kRankSlots; ++sl) {
+          const unsigned long long other = (j == 64) ? rec[sl ^ 1] : rec[sl ^ 2];
+          nxt[sl] = keep(rec[sl], other, e0 + 64 * sl, j, k);
+        }
+#pragma unroll
+        for (int sl = 0; sl < kRankSlots; ++sl)
+          if (sl < slots) rec[sl] = nxt[sl];
+      } else {
+#pragma unroll
+        for (int sl = 0; sl < kRankSlots; ++sl) {
+          const unsigned long long other = __shfl_xor(rec[sl], j);
+          rec[sl] = keep(rec[sl], other, e0 + 64 * sl, j, k);
+        }
       }
     }
   }
-  __syncthreads();
+  if (in_lds) {
+    __syncthreads();
+  } else {
+    // (nobody reads `ranked` before the barrier below, and the last stage that wrote it
+    // was followed by a barrier and a reload)
+#pragma unroll
+    for (int sl = 0; sl < kRankSlots; ++sl)
+      if (active && sl < slots) ranked[e0 + 64 * sl] = rec[sl];
+    __syncthreads();
+  }
 }
 
 // The rest of a step once this workgroup's scores are in memory (and a barrier has been
