@@ -282,7 +282,10 @@ def main() -> int:
                         traffic=MEASURED_TRAFFIC.get(w.name, {}).get(dom) if default_options else None,
                         traffic_source=TRAFFIC_SOURCE.get(dom) if default_options and w.name in MEASURED_TRAFFIC else None,
                         bytes_per_launch=bytes_per_launch, avg_launch_us=kernels[dom]["avg_us"],
-                        launches_per_step=launches, profiled_ms_per_step=prof_ms)
+                        launches_per_step=launches, profiled_ms_per_step=prof_ms,
+                        note="priced against HBM as the path's contract asks; counters and microbenchmarks "
+                             "(profiles/) show the scoring passes bound by vector/matrix instruction issue, "
+                             "not by memory")
 
     # what the arithmetic side of the same launches amounts to (bf16 runs; information
     # beside the contract's HBM figure: the scoring passes are not bound by memory)
