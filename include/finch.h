@@ -276,7 +276,15 @@ typedef enum {
    * no more problems than the chip has compute units: the L workgroups of a run then
    * wait for each other's scores inside the launch (see finch_workspace_status);
    * other batches run with one kernel per stage. */
-  FINCH_OPT_LAYER_GROUP = 4
+  FINCH_OPT_LAYER_GROUP = 4,
+  /* how long a workgroup waits for the others of its layer before it gives up, in ticks
+   * of the GPU's 100 MHz wall clock: 0 .. 10^9, default 2 * 10^7 (0.2 s).  A wait that
+   * expires sets the workspace's status word (finch_workspace_status); the workgroup
+   * leaves that step's indices and cache rows unwritten and the launch goes on to its
+   * end: nothing is written outside its buffers, but indices and caches of that call are
+   * not to be used.  0 makes the first workgroup of every layer give up at once: the way
+   * to exercise the error path. */
+  FINCH_OPT_LAYER_WAIT_TICKS = 5
 } finch_option;
 typedef enum { FINCH_PATH_AUTO = 0, FINCH_PATH_SEPARATE = 1, FINCH_PATH_OWNER = 3 } finch_path;
 finch_status finch_set_option(finch_ctx* ctx, int32_t option, int64_t value);

@@ -43,6 +43,7 @@ KERNEL_NAMES = ("rowstats", "lse", "colsum", "select", "gather", "owner", "promp
 FINCH_OPT_STEP_PATH = 1
 FINCH_OPT_SLICE_KEYS = 3
 FINCH_OPT_LAYER_GROUP = 4
+FINCH_OPT_LAYER_WAIT_TICKS = 5
 FINCH_SCHEDULE_PROPORTIONAL, FINCH_SCHEDULE_CONSTANT = 0, 1
 FINCH_PATH_AUTO = 0
 FINCH_PATH_SEPARATE = 1

@@ -28,6 +28,7 @@ struct finch_ctx {
   int slice_keys;        // target keys per workgroup slice of the bf16 scoring kernels
   finch_reposition repos;  // {OFF, ASCENDING}: plain copies
   int layer_group;         // > 1: runs of that many problems share one selection
+  int64_t layer_wait_ticks;  // bound of a workgroup's wait for its layer, 100 MHz ticks
   void* static_scratch;    // this device's copy of the file-scope scratch array (finch_step_static)
   // finch_loop: fingerprint of the last descriptor set whose slots were found free of
   // overlaps (the check is repeated only when the descriptors change)
@@ -248,7 +249,7 @@ LaunchParams make_params(const finch_ctx* ctx, const finch_problem* dd, int32_t 
   p.layer_group = ctx->layer_group;
   p.layer_sync = base ? reinterpret_cast<int32_t*>(base + pl.off_sync) : nullptr;
   p.layer_err = reinterpret_cast<int32_t*>(base);
-  p.spin_ticks = 20 * 1000 * 1000;  // 0.2 s
+  p.spin_ticks = ctx->layer_wait_ticks;
   return p;
 }
 
@@ -579,6 +580,7 @@ finch_status finch_create(const finch_config* cfg, finch_ctx** out) {
   ctx->step_path = FINCH_PATH_AUTO;
   ctx->slice_keys = finch::kDefaultSliceKeys;
   ctx->layer_group = 1;
+  ctx->layer_wait_ticks = 20 * 1000 * 1000;  // 0.2 s
   ctx->repos.pairing = FINCH_ROPE_OFF;
   ctx->repos.order = FINCH_ORDER_ASCENDING;
   ctx->repos.base = 10000.0;
@@ -633,6 +635,10 @@ finch_status finch_set_option(finch_ctx* ctx, int32_t option, int64_t value) {
     case FINCH_OPT_LAYER_GROUP:
       if (value < 1 || value > 4096) return FINCH_ERR_INVALID_ARG;
       ctx->layer_group = static_cast<int>(value);
+      return FINCH_OK;
+    case FINCH_OPT_LAYER_WAIT_TICKS:
+      if (value < 0 || value > 1000000000) return FINCH_ERR_INVALID_ARG;
+      ctx->layer_wait_ticks = value;
       return FINCH_OK;
     case FINCH_OPT_SLICE_KEYS:
       if (value < 256 || value > (1 << 24)) return FINCH_ERR_INVALID_ARG;

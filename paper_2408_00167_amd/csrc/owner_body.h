@@ -287,13 +287,16 @@ __device__ __forceinline__ void own_finish_step(const LaunchParams& prm, const f
       if (tid == 0) {
         __hip_atomic_fetch_add(sync_words, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const long long t0 = wall_clock64();
+        int gave_up = 0;
         while (__hip_atomic_load(sync_words, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < L * (epoch + 1)) {
           __builtin_amdgcn_s_sleep(8);
           if (wall_clock64() - t0 > prm.spin_ticks) {
             atomicOr(prm.layer_err, 1);
+            gave_up = 1;
             break;
           }
         }
+        fl->layer_gave_up = gave_up;
       }
       if (tid < L) {
         const finch_problem pg = step_probs[run * L + tid];
@@ -301,6 +304,14 @@ __device__ __forceinline__ void own_finish_step(const LaunchParams& prm, const f
                                        : prm.ws_scores + static_cast<size_t>(run * L + tid) * prm.score_stride;
       }
       __syncthreads();
+      if (fl->layer_gave_up) {
+        // Scores that other workgroups are still writing must not be selected on (a
+        // selection that reads them twice could count differently each time): this
+        // workgroup leaves the step's indices and cache rows unwritten.  It still says
+        // that it will not read the others' scores any more.
+        if (tid == 0) __hip_atomic_fetch_add(sync_words + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+      }
     }
     const LayerScores layer_sum = {fl->layer_src, L};
     const OneScoreVector own = {dst};

@@ -45,6 +45,7 @@ struct SelLds {  // LDS scratch of a selection
   int wave_tot[2][kSelMaxWaves];
   int digit[4], remaining[4];
   const float* layer_src[kSelMaxLayer];  // LayerScores: the score vectors of a layer's heads
+  int layer_gave_up;                     // the wait for the layer's other workgroups expired
 };
 
 // Where a selection takes the score of candidate i from: one vector ...

@@ -89,6 +89,42 @@ def test_layer_wise_selection(dtype, d, group, L, path):
     fin.close()
 
 
+def test_a_wait_that_expires_is_reported():
+    """The bound on a workgroup's wait for its layer, forced from the host: with a bound of 0
+    ticks the first workgroup of a layer to arrive gives up at once and leaves its indices
+    unwritten, the launch still runs to its end, and finch_workspace_status reports it; with
+    the default bound the same batch runs clean again."""
+    say("layer wait bound")
+    fin = F.Finch(F.FINCH_BF16, 128, 4)
+    fin.set_step_path(F.FINCH_PATH_OWNER)
+    F.finch_set_option(fin.ctx, F.FINCH_OPT_LAYER_GROUP, 8)
+    specs = [sp for sp in LAYERS for _ in range(8)]
+    F.finch_set_option(fin.ctx, F.FINCH_OPT_LAYER_WAIT_TICKS, 0)
+    b0, t0 = H.single_step_case(fin, specs, torch.bfloat16, 128, 4, seed=77)
+    fin.step(b0)
+    with pytest.raises(F.FinchError) as e:
+        fin.workspace_status()
+    assert e.value.status == F.FINCH_ERR_TIMEOUT
+    untouched = 0
+    for t in t0:   # a workgroup that gave up wrote no indices; the others wrote theirs inside the buffer
+        rr = min(t["r"], t["c"] + t["m"])
+        idx = t["idx"][:rr].cpu().numpy()
+        if rr and (idx == -9).all():
+            untouched += 1
+        else:
+            assert ((idx >= 0) & (idx < t["c"] + t["m"])).all()
+        assert int(t["idx"][max(rr, 1)]) == -9
+    assert untouched >= 1
+    F.finch_set_option(fin.ctx, F.FINCH_OPT_LAYER_WAIT_TICKS, 20_000_000)
+    b1, t1 = H.single_step_case(fin, specs, torch.bfloat16, 128, 4, seed=77)
+    fin.step(b1)
+    assert fin.workspace_status() == 0
+    say(f"  swaps {validate_layers(t1, 8, 'after the bound was restored')}")
+    with pytest.raises(F.FinchError):
+        F.finch_set_option(fin.ctx, F.FINCH_OPT_LAYER_WAIT_TICKS, -1)
+    fin.close()
+
+
 def test_layer_group_argument_checks():
     fin = F.Finch(F.FINCH_BF16, 128, 4)
     F.finch_set_option(fin.ctx, F.FINCH_OPT_LAYER_GROUP, 2)
