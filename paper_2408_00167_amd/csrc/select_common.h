@@ -178,7 +178,10 @@ __device__ __forceinline__ void select_generic(const unsigned* keys, const Src& 
     const int eq_rank = carry_eq + sel_block_rank<NT>(eq, f->wave_tot[0], lane, wave, tot_eq);
     const bool keep = gt || (eq && eq_rank < need_eq);
     const int pos = carry_keep + sel_block_rank<NT>(keep, f->wave_tot[0], lane, wave, tot_keep);
-    if (keep) {
+    // (pos < r always when the scores hold still; if another workgroup is overwriting them -
+    // a layer's workgroup whose bounded wait has expired - the rounds may have counted
+    // different values, and nothing may be written past the r places of the output)
+    if (keep && pos < r) {
       gidx[pos] = i;
       if (lidx) lidx[pos] = i;
     }
