@@ -15,7 +15,10 @@ against a CPU reference and times them at the size of the C4 workload.
 Environment switches for the stripped variants that show where the time goes: NOLOAD=1 (no key loads),
 NOQREAD=1 (no LDS reads: the matrix instructions take stale operands), NOVALU=1 (no vector work),
 NOMFMA=1 (no matrix instructions), NOBRANCH=1.  Results of stripped variants are wrong on purpose;
-run the harness with the argument `time` then.
+run the harness with the argument `time` then.  FAIR=1 adds a feedback between the two waves of a
+SIMD (waves w and w + 4): each publishes the number of blocks it has done in LDS once per block, reads
+the other's, and takes the higher issue priority (s_setprio) while it is not ahead; without it the
+wave that was launched first wins the arbitration and finishes 15-20 us before the other.
 
   python pass_asm.py && hipcc --offload-arch=gfx950 -O3 -Xclang -target-feature -Xclang -packed-fp32-ops \
       -o pass_asm_harness pass_asm_harness.hip && ./pass_asm_harness
@@ -26,6 +29,7 @@ NOVALU = os.environ.get('NOVALU') == '1'
 NOMFMA = os.environ.get('NOMFMA') == '1'
 NOBRANCH = os.environ.get('NOBRANCH') == '1'
 NOQREAD = os.environ.get('NOQREAD') == '1'
+FAIR = os.environ.get('FAIR') == '1'
 
 D = 128
 KS = D // 16          # k-steps of 16 per 32x32x16 MFMA
@@ -58,6 +62,9 @@ class Regs:
         self.SEND = v; v += 1
         self.ZZ = v; v += 1
         self.TOT = v; v += 1
+        self.PW = v; v += 1
+        self.PR = v; v += 1
+        self.PS = v; v += 1
         self.vtop = v
         assert v <= 246, v
         assert 2 * QB <= 16 and QB <= 8
@@ -253,6 +260,10 @@ def section(R, mode, buf, sec, tag):
     beginning of its own)"""
     L = []
     L.append("s_waitcnt vmcnt(0)")          # this block's keys (requested during the section before)
+    if FAIR:
+        L.append(f"v_mov_b32 v{R.PW}, s{S_SEQ}")
+        L.append(f"ds_write_b32 %[paddr], v{R.PW}")
+        L.append(f"ds_read_b32 v{R.PR}, v{R.PS}")
     loads = [] if NOLOAD else load_block(R, (buf + 1) % 2, 1)
     scalar = [x for x in loads if not x.startswith("global_load")]
     vmem = [x for x in loads if x.startswith("global_load")]
@@ -282,6 +293,16 @@ def section(R, mode, buf, sec, tag):
                 L.append(op)
         if prev and ops and not NOBRANCH:
             L.append(f"{tag}{sec}{k:02d}:")
+    if FAIR:
+        # whoever of the SIMD's two waves is behind takes the higher priority for the next block
+        L.append(f"v_readfirstlane_b32 s{S_T2}, v{R.PR}")
+        L.append(f"s_cmp_le_u32 s{S_SEQ}, s{S_T2}")
+        L.append(f"s_cbranch_scc0 {tag}{sec}97f")
+        L.append("s_setprio 3")
+        L.append(f"s_branch {tag}{sec}98f")
+        L.append(f"{tag}{sec}97:")
+        L.append("s_setprio 0")
+        L.append(f"{tag}{sec}98:")
     L.append(f"s_add_u32 s{S_SEQ}, s{S_SEQ}, 1")
     return L
 
@@ -308,6 +329,8 @@ def emit(QB, mode):
         for q in range(QB):
             L.append(f"ds_read_b32 v{R.NEGL + q}, %[laddr] offset:{q * 128}")
     L.append(f"s_mov_b32 s{S_SEQ}, 0")
+    if FAIR:
+        L.append(f"v_xor_b32 v{R.PS}, 16, %[paddr]")
     L.append(f"s_mov_b32 s{S_B1}, 0xcccccccc")
     L.append(f"s_mov_b32 s{S_B1 + 1}, 0xcccccccc")
     # the first prompt-row operands into the ring
@@ -345,6 +368,8 @@ def emit(QB, mode):
             L.append(f"v_add_f32 v{z}, v{z}, v{z + 1}")
         for q in range(QB):
             L.append(f"ds_write_b32 %[zaddr], v{R.Z + 2 * q} offset:{q * 256}")
+    if FAIR:
+        L.append("s_setprio 0")
     L.append("s_waitcnt vmcnt(0) lgkmcnt(0)")
     return R, L
 
@@ -356,13 +381,13 @@ def function(QB, mode):
     sclob = ",".join(f'"s{i}"' for i in range(64, 80))
     if mode == 2:
         sig = ("const void* kcache, const void* kchunk, float* scores, int c, int nbc, int nbtot, int wave, int nw, "
-               "float sc, unsigned qaddr, unsigned laddr, unsigned rowoff, unsigned stoff")
+               "float sc, unsigned qaddr, unsigned laddr, unsigned rowoff, unsigned stoff, unsigned paddr")
         extra_in = ', [sp_lo] "s"(sp_lo), [sp_hi] "s"(sp_hi), [c] "s"(c), [stoff] "v"(stoff)'
         pre = ("  const unsigned sp_lo = U((unsigned)(unsigned long long)scores), sp_hi = U((unsigned)((unsigned long long)scores >> 32));\n"
                "  c = (int)U(c);\n")
     else:
         sig = ("const void* kcache, const void* kchunk, int nbc, int nbtot, int wave, int nw, "
-               "float sc, unsigned qaddr, unsigned laddr, unsigned rowoff, unsigned zaddr")
+               "float sc, unsigned qaddr, unsigned laddr, unsigned rowoff, unsigned zaddr, unsigned paddr")
         extra_in = ', [zaddr] "v"(zaddr)'
         pre = ""
     return f'''
@@ -381,7 +406,7 @@ __device__ __forceinline__ void {name}({sig}) {{
       :
       : [kc_lo] "s"(kc_lo), [kc_hi] "s"(kc_hi), [kk_lo] "s"(kk_lo), [kk_hi] "s"(kk_hi), [nbc] "s"(nbc),
         [nbtot] "s"(nbtot), [wave] "s"(wave), [nw] "s"(nw), [sc] "s"(sc), [qaddr] "v"(qaddr),
-        [laddr] "v"(laddr), [rowoff] "v"(rowoff){extra_in}
+        [laddr] "v"(laddr), [rowoff] "v"(rowoff), [paddr] "v"(paddr){extra_in}
       : {vclob},
         {sclob}, "scc", "vcc", "memory");
 }}

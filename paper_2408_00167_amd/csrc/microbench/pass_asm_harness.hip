@@ -12,7 +12,7 @@
 constexpr int QB = 6, R = QB * 32, Dh = 128, QS = Dh * 2 + 16;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-// LDS: Q rows [R][QS], then negL [R] floats, then zbuf [4][QB][64] floats
+// LDS: Q rows [R][QS], then negL [R] floats, then zbuf [8][QB][64] floats, then 8 progress words (FAIR=1)
 __global__ __launch_bounds__(512) void k_pass(int mode, const char* Q, const float* negl, const char* Kc, const char* Kk,
                                                 size_t kc_stride, size_t kk_stride, float* scores, size_t sc_stride,
                                                 float* zout, int c, int m, float sc, int fake_nw, unsigned long long* tick) {
@@ -25,6 +25,9 @@ __global__ __launch_bounds__(512) void k_pass(int mode, const char* Q, const flo
   float* lneg = (float*)(smem + R * QS);
   float* zbuf = lneg + R;
   for (int i = tid; i < R; i += 512) lneg[i] = negl[i];
+  unsigned* prog = (unsigned*)(zbuf + 8 * QB * 64);
+  if (tid < 8) prog[tid] = 0;
+  const unsigned paddr = (unsigned)(size_t)(prog) + 4 * wave;
   __syncthreads();
   const int nbc = c / 32, nbk = m / 32, nbtot = nbc + nbk;
   int nw = wave < nbtot ? (nbtot - wave + 7) / 8 : 0;
@@ -40,8 +43,8 @@ __global__ __launch_bounds__(512) void k_pass(int mode, const char* Q, const flo
   const unsigned stoff = 4 * (8 * (v >> 2) + 4 * h + (v & 3));
   const unsigned long long t0 = wall_clock64();
   if (nw > 0) {
-    if (mode == 2) pass2_asm_qb6(kc, kk, sp, c, nbc, nbtot, wave, nw, sc, qaddr, laddr, rowoff, stoff);
-    else pass1_asm_qb6(kc, kk, nbc, nbtot, wave, nw, sc, qaddr, laddr, rowoff, zaddr);
+    if (mode == 2) pass2_asm_qb6(kc, kk, sp, c, nbc, nbtot, wave, nw, sc, qaddr, laddr, rowoff, stoff, paddr);
+    else pass1_asm_qb6(kc, kk, nbc, nbtot, wave, nw, sc, qaddr, laddr, rowoff, zaddr, paddr);
   }
   const unsigned long long t1 = wall_clock64();
   if (tick && lane == 0) { tick[blockIdx.x * 8 + wave] = t1 - t0; }
@@ -93,7 +96,7 @@ int main(int argc, char** argv) {
     CK(hipMemcpy(dKc, hKc.data(), hKc.size() * 2, hipMemcpyHostToDevice));
     CK(hipMemcpy(dKk, hKk.data(), hKk.size() * 2, hipMemcpyHostToDevice));
     CK(hipMemset(dS, 0xff, (N + 64) * 4));
-    const size_t lds = R * QS + R * 4 + 8 * QB * 64 * 4 ;
+    const size_t lds = R * QS + R * 4 + 8 * QB * 64 * 4 + 32 ;
     CK(hipFuncSetAttribute((const void*)k_pass, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     // pass 2
     CK(hipMemcpy(dL, negl.data(), R * 4, hipMemcpyHostToDevice));
@@ -146,7 +149,7 @@ int main(int argc, char** argv) {
     CK(hipMemcpy(dQ, hQ.data(), hQ.size() * 2, hipMemcpyHostToDevice));
     std::vector<float> negl(R, -12.f);
     CK(hipMemcpy(dL, negl.data(), R * 4, hipMemcpyHostToDevice));
-    const size_t lds = R * QS + R * 4 + 8 * QB * 64 * 4 ;
+    const size_t lds = R * QS + R * 4 + 8 * QB * 64 * 4 + 32 ;
     unsigned long long* dT; CK(hipMalloc(&dT, WG * 8 * 8));
     hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
     for (int mode = 1; mode <= 2; ++mode)
@@ -165,6 +168,7 @@ int main(int argc, char** argv) {
         double avg = 0, mx = 0;
         for (int i = 0; i < WG * 8; ++i) { auto x = hT[i]; avg += x; if (x > mx) mx = x; }
         avg /= WG * 8;
+        { double pw[8] = {0}; for (int i = 0; i < WG * 8; ++i) pw[i % 8] += hT[i]; printf("   per wave index (us):"); for (int w = 0; w < 8; ++w) printf(" %.1f", pw[w] / WG / 100.0); printf("\n"); }
         printf("pass %d, region stride %zu: %.1f us per launch; inside the loop call mean %.1f us, slowest wave %.1f us; %.2f TB/s of keys\n",
                mode, stride, us, avg / 100.0, mx / 100.0, WG * kbytes / us * 1e-6);
         fflush(stdout);
