@@ -86,9 +86,9 @@ def load_library() -> ctypes.CDLL:
     if _lib is not None:
         return _lib
     if not os.path.exists(LIB_PATH):
-        raise FileNotFoundError(
-            f"{LIB_PATH} is missing: build it with `python -m paper_2408_00167_amd.build` "
-            "(there is no fallback path)")
+        how = ("python -m paper_2408_00167_amd.build --phase-timers" if LIB_PATH.endswith("libfinch_phases.so")
+               else "python -m paper_2408_00167_amd.build")
+        raise FileNotFoundError(f"{LIB_PATH} is missing: build it with `{how}` (there is no fallback path)")
     lib = ctypes.CDLL(LIB_PATH)
     P = ctypes.POINTER
     vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
