@@ -172,7 +172,7 @@ def main() -> int:
 
     if not os.path.exists(F.LIB_PATH):
         from paper_2408_00167_amd.build import build_library
-        build_library(verbose=False)
+        build_library(verbose=False, phase_timers=args.phases)
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; there is no CPU path", file=sys.stderr)
         return 3
