@@ -125,8 +125,9 @@ def cpu_baseline(w, next_problem, chunk, budget_s=10.0, seed=12345):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=20)
+    # (the first launches after the inputs have been drawn run 5-20 % longer than the steady state)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C4")
     ap.add_argument("--path", default="auto", choices=["auto", "separate", "owner"],
                     help="launch path of the library (auto: its own choice)")
