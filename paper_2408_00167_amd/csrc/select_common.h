@@ -103,6 +103,38 @@ __device__ __forceinline__ void sel_pick_digit(const int* hist, int remaining, i
   }
 }
 
+// The same by every wave for itself (all waves read the same histogram and get the same
+// answer, so nothing has to be handed round through LDS and no barrier follows): the bin
+// where the count from the top reaches `remaining`, and the rank left inside it.
+__device__ __forceinline__ void sel_pick_digit_wave(const int* hist, int remaining, int lane, int& digit_out,
+                                                    int& left_out) {
+  const int h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
+  const int mine = h0 + h1 + h2 + h3;
+  const int prefix = wave_inclusive_scan(mine);
+  const int total = __builtin_amdgcn_readlane(prefix, 63);
+  const int suffix = total - prefix + mine;  // inclusive sum over lanes >= this one
+  const int above = suffix - mine;           // keys in bins of higher lanes
+  const bool found = above < remaining && remaining <= suffix;
+  int left = remaining - above, digit = 3;
+  if (left > h3) {
+    if (left <= h3 + h2) {
+      digit = 2;
+      left -= h3;
+    } else if (left <= h3 + h2 + h1) {
+      digit = 1;
+      left -= h3 + h2;
+    } else {
+      digit = 0;
+      left -= h3 + h2 + h1;
+    }
+  }
+  // (exactly one lane finds it when 0 < remaining <= total; lane 0's values otherwise)
+  const unsigned long long m = __ballot(found);
+  const int src = m ? __ffsll(static_cast<long long>(m)) - 1 : 0;
+  digit_out = __shfl(4 * lane + digit, src);
+  left_out = __shfl(left, src);
+}
+
 // Exclusive rank of `flag` among the workgroup's threads in thread order, and the
 // total.  Two barriers; every thread must call it.
 template <int NT>
@@ -228,11 +260,10 @@ __device__ __forceinline__ void select_regs(const Src& score_of, int N, int r,
       }
     }
     __syncthreads();
-    if (wave == 0) sel_pick_digit(hist, remaining, lane, &f->digit[round], &f->remaining[round]);
-    __syncthreads();
-    prefix |= static_cast<unsigned>(f->digit[round]) << shift;
+    int digit;
+    sel_pick_digit_wave(hist, remaining, lane, digit, remaining);
+    prefix |= static_cast<unsigned>(digit) << shift;
     mask |= 255u << shift;
-    remaining = f->remaining[round];
   }
   const unsigned T = prefix;
   const int need_eq = remaining;  // candidates equal to T that are kept (>= 1)
