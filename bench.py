@@ -36,11 +36,11 @@ TRAFFIC_SOURCE = {"owner": "profiles/owner_loop_bf16_C4_hbm_traffic.txt",
                   "select": "profiles/stage_kernels_bf16_C4_hbm_traffic.txt",
                   "gather": "profiles/stage_kernels_bf16_C4_hbm_traffic.txt"}
 MEASURED_TRAFFIC = {"C4": {
-    "rowstats": 2.0 * 159880.1 * 1024 + 1792.0 * 1024,
-    "colsum": 2.0 * 159517.3 * 1024 + 4780.0 * 1024,
-    "select": 2.0 * 2563.3 * 1024 + 728.0 * 1024,
-    "gather": 2.0 * 47163.3 * 1024 + 92928.0 * 1024,
-    "owner": 2.0 * 11121424.3 * 1024 + 3149952.0 * 1024,   # one launch = the whole loop
+    "rowstats": 2.0 * 159749.1 * 1024 + 1792.0 * 1024,
+    "colsum": 2.0 * 159516.2 * 1024 + 4780.0 * 1024,
+    "select": 2.0 * 2557.3 * 1024 + 728.0 * 1024,
+    "gather": 2.0 * 47163.0 * 1024 + 92928.0 * 1024,
+    "owner": 2.0 * 11133278.1 * 1024 + 3149952.0 * 1024,   # one launch = the whole loop
 }}
 
 
