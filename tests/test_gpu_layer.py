@@ -89,6 +89,58 @@ def test_layer_wise_selection(dtype, d, group, L, path):
     fin.close()
 
 
+@pytest.mark.parametrize("dtype,d,group,L,path", [(torch.bfloat16, 128, 4, 8, "owner"), (torch.bfloat16, 128, 4, 8, "separate"),
+                                                  (torch.bfloat16, 64, 2, 4, "owner"), (torch.float32, 64, 1, 2, "owner"),
+                                                  (torch.float32, 64, 1, 2, "separate")])
+def test_the_papers_own_configuration(dtype, d, group, L, path):
+    """The options together, as the paper words the method: the prompt's own keys in the
+    denominator, the scores summed over the heads of a layer and one top-r per layer, kept keys
+    re-positioned (ascending slots) while they are compacted."""
+    say(f"paper-literal {dtype} d={d} G={group} L={L} {path}")
+    base = 10000.0
+    fin = F.Finch(H.finch_dtype(torch.empty(0, dtype=dtype)), d, group)
+    fin.set_step_path(F.FINCH_PATH_OWNER if path == "owner" else F.FINCH_PATH_SEPARATE)
+    F.finch_set_option(fin.ctx, F.FINCH_OPT_LAYER_GROUP, L)
+    fin.set_reposition(F.FINCH_ROPE_HALF, F.FINCH_ORDER_ASCENDING, base)
+    layers = [dict(n_que=24, c=300, m=1000, r=200), dict(n_que=5, c=37, m=255, r=100),
+              dict(n_que=16, c=100, m=156, r=256), dict(n_que=9, c=0, m=700, r=33)]
+    if dtype == torch.float32:
+        layers = [dict(sp, n_que=min(sp["n_que"], 8)) for sp in layers]
+    specs = [dict(sp, prompt_keys=True) for sp in layers for _ in range(L)]
+    batch, ts = H.single_step_case(fin, specs, dtype, d, group, seed=4242 + L)
+    fin.prompt_lse(batch)
+    fin.step(batch)
+    torch.cuda.synchronize()
+    assert fin.workspace_status() == 0
+    tol = H.SCORE_TOL[H.dtype_name(ts[0]["k_out"])]
+    swaps, worst_rot = 0, 0.0
+    for run in range(len(ts) // L):
+        heads = ts[run * L:(run + 1) * L]
+        t0 = heads[0]
+        N, r = t0["c"] + t0["m"], t0["r"]
+        rr = min(r, N)
+        per_head = []
+        for t in heads:
+            want_extra = O.prompt_lse(W.to_numpy_storage(t["q"]), W.to_numpy_storage(t["k_que"]), group)
+            extra = t["lse_extra"][:-1].double().cpu().numpy()
+            assert np.abs(extra - want_extra).max() < 1e-5 * max(1.0, np.abs(want_extra).max())
+            # (the scoring is checked with the term the GPU was given, itself checked just above)
+            want = O.key_scores(W.to_numpy_storage(t["q"]), W.to_numpy_storage(t["k_cache"]),
+                                W.to_numpy_storage(t["k_chunk"]), lse_extra=extra)
+            H.check_scores(t["scores"].cpu().numpy()[:N], want, tol, f"run {run}")
+            per_head.append(want)
+        idx = t0["idx"].cpu().numpy()
+        swaps += H.check_indices(idx[:rr], O.layer_scores(per_head), r, f"run {run}")
+        for t in heads:
+            assert torch.equal(t["idx"], t0["idx"]), f"run {run}: heads disagree"
+            Kc, Kk = W.to_numpy_storage(t["k_cache"]), W.to_numpy_storage(t["k_chunk"])
+            Vc, Vk = W.to_numpy_storage(t["v_cache"]), W.to_numpy_storage(t["v_chunk"])
+            worst_rot = max(worst_rot, H.check_repositioned(t, Kc, Kk, Vc, Vk, idx, rr, "half", "ascending", base,
+                                                            f"run {run}"))
+    say(f"  swaps {swaps}, worst rotation error / row max {worst_rot:.2e}")
+    fin.close()
+
+
 def test_a_wait_that_expires_is_reported():
     """The bound on a workgroup's wait for its layer, forced from the host: with a bound of 0
     ticks the first workgroup of a layer to arrive gives up at once and leaves its indices
